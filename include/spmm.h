@@ -1,0 +1,194 @@
+/*
+ * Brick SpMM for MI355X (gfx950): C = A . B with A sparse (CSR in, 16-row panels
+ * of column-compacted 16x4 bricks inside), B and C dense row-major fp32.
+ *
+ * C ABI.  Every function returns an spmm_status (0 = success, negative = error),
+ * never throws, aborts or prints; spmm_last_error() gives a thread-local message.
+ * "dev" pointers are HIP device pointers on the current device, "host" pointers
+ * are ordinary host memory.  The library never takes ownership of caller memory.
+ *
+ * Paper: arxiv 2504.06443.  Section 3.1 defines the operation and the layouts,
+ * Section 3.2 the panel/brick format, Section 3.3 / Algorithm 1 the kernel,
+ * Section 4 the operational-intensity model, Section 5 the load balancer,
+ * Section 6.4 / Table 1 the synergy classes.
+ */
+#ifndef SPMM_H_
+#define SPMM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spmm_plan spmm_plan_t; /* opaque; owns every device/host buffer it creates */
+
+enum spmm_status {
+  SPMM_OK = 0,
+  SPMM_EINVAL = -1,  /* null pointer, negative size, bad enum value                          */
+  SPMM_EFORMAT = -2, /* CSR not valid: rowptr not monotone / wrong ends, column out of range,
+                        columns of a row not strictly ascending                              */
+  SPMM_ENOMEM = -3,  /* host or device allocation failed                                     */
+  SPMM_EHIP = -4,    /* a HIP call failed; text in spmm_last_error()                         */
+  SPMM_ELIMIT = -5   /* nnz >= 2^31, 4*bricks >= 2^32 or M >= 2^31                           */
+};
+
+enum spmm_route {
+  SPMM_ROUTE_AUTO = 0, /* Low-synergy panels (Table 1, per panel) -> vector-ALU CSR kernel,
+                          Medium/High -> MFMA brick kernel                                    */
+  SPMM_ROUTE_MFMA = 1, /* every non-empty panel through the MFMA brick kernel                 */
+  SPMM_ROUTE_VALU = 2  /* every panel through the vector-ALU CSR kernel                       */
+};
+
+enum spmm_class { SPMM_NONE = -1, SPMM_LOW = 0, SPMM_MEDIUM = 1, SPMM_HIGH = 2 };
+
+/* ---------------------------------------------------------------------------
+ * spmm_plan -- CSR -> brick format (Section 3.2), built by HIP kernels.
+ *
+ *   M, K     rows / columns of A (>= 0, M < 2^31)
+ *   nnz      stored entries (0 <= nnz < 2^31); must equal rowptr[M]
+ *   rowptr   dev int32[M+1], rowptr[0] = 0, non-decreasing
+ *   colind   dev int32[nnz], inside each row strictly ascending, 0 <= col < K
+ *   vals     dev float[nnz]; explicitly stored zeros are kept as entries
+ *   stream   hipStream_t (NULL = default stream); all work is enqueued there
+ *   out      receives the plan; destroy with spmm_plan_destroy
+ *
+ * The CSR arrays are only read during the call (the plan keeps its own copies of
+ * what it needs later) and may be freed after it returns.  The call synchronises
+ * `stream` several times (it reads back sizes to allocate).  The input is
+ * validated on the device first; an invalid CSR gives SPMM_EFORMAT and no plan.
+ *
+ * Format (panel p = rows 16p..16p+15; P = ceil(M/16) panels; nb bricks):
+ *   panel_ptr    u32[P+1]  first brick of each panel
+ *   brick_cols   u32[4 nb] original column of each brick column; a panel's active
+ *                          columns in ascending order, four per brick, the last
+ *                          brick padded with 0xFFFFFFFF
+ *   brick_mask   u64[nb]   bit 4*r+c set <=> element (row r, brick column c) stored
+ *   brick_valptr u32[nb+1] start of each brick's values
+ *   vals         f32[nnz]  values of each brick in ascending bit order (row-major)
+ */
+int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t *rowptr, const int32_t *colind,
+              const float *vals, void *stream, spmm_plan_t **out);
+
+/* ---------------------------------------------------------------------------
+ * spmm_exec -- C = A . B (Section 3.1; Algorithm 1 re-designed for MFMA).
+ *
+ *   B   dev float[K*N], row-major, leading dimension N; must be finite (zero
+ *       filling multiplies every B row of an active column by explicit zeros)
+ *   N   columns of B and C, >= 0
+ *   C   dev float[M*N], row-major, leading dimension N; fully overwritten (rows
+ *       of A without entries become zero); must not overlap B
+ *   stream  hipStream_t; the call only enqueues kernels and returns
+ *
+ * fp32 multiply, fp32 accumulate (no reduced-precision rounding of inputs).  The
+ * result is deterministic for a given plan, N and device.  The first call for a
+ * new N builds and caches that N's work list (a host computation plus one small
+ * upload, which synchronises the stream once); later calls allocate nothing.
+ * A plan must not be used by two spmm_exec calls at the same time.
+ */
+int spmm_exec(spmm_plan_t *plan, const float *B, int64_t N, float *C, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * spmm_synergy -- brick density, modeled operational intensity and synergy class
+ * (Section 4, Eq. 4; Section 6.4, Table 1), plus an HBM / MFMA roofline model
+ * for MI355X.  Pure host arithmetic on counts gathered at plan time.
+ */
+typedef struct spmm_synergy {
+  /* integer counts: reproducible bit for bit */
+  int64_t M, K, nnz;
+  int64_t n_panels;          /* P = ceil(M/16)                                   */
+  int64_t n_nonempty_panels; /* panels with at least one brick                   */
+  int64_t n_bricks;          /* nb                                               */
+  int64_t n_active_cols;     /* sum over panels of distinct columns              */
+  int64_t n_distinct_cols;   /* distinct columns of the whole matrix             */
+  int64_t panels_by_class[3]; /* per-panel class, Low/Medium/High (empty: none)  */
+  int64_t bricks_by_class[3];
+  int64_t nnz_by_class[3];
+  int64_t brick_pop_hist[65]; /* bricks by number of stored elements             */
+  int32_t synergy_class;      /* spmm_class of the whole matrix from alpha_brick */
+  int32_t reserved_;
+  /* model */
+  double alpha_brick;      /* nnz / (64 nb): brick density (Section 4)           */
+  double alpha_col;        /* nnz / (16 n_active_cols): density of active columns */
+  double beta;             /* bricks per brick column; 1 for 16-row panels       */
+  double oi_shmem;         /* 512 alpha beta (Eq. 4, Eq. 5)                      */
+  double bytes_min;        /* 4 nnz + 28 nb + 4 + 4 (P+1) + 4 N n_distinct_cols + 4 N M */
+  double bytes_noreuse;    /* same with n_active_cols in place of n_distinct_cols */
+  double oi_hbm_min;       /* 2 nnz N / bytes_min   (flop per HBM byte)          */
+  double oi_hbm_noreuse;   /* 2 nnz N / bytes_noreuse                            */
+  double roof_gflops_hbm;  /* oi_hbm_min * 8e12 B/s, in GFLOP/s                  */
+  double roof_gflops_mfma; /* alpha_brick * 157.3e12 flop/s, in GFLOP/s          */
+} spmm_synergy_t;
+
+int spmm_synergy(const spmm_plan_t *plan, int64_t N, spmm_synergy_t *out /* host */);
+
+/* ---------------------------------------------------------------------------
+ * Format export (tests, debugging).  spmm_plan_sizes fills counts; then
+ * spmm_plan_export copies each array into host buffers of those sizes
+ * (any pointer may be NULL to skip that array).  Synchronises the device.
+ */
+typedef struct spmm_sizes {
+  int64_t M, K, nnz, n_panels, n_bricks;
+} spmm_sizes_t;
+
+int spmm_plan_sizes(const spmm_plan_t *plan, spmm_sizes_t *out /* host */);
+int spmm_plan_export(const spmm_plan_t *plan, uint32_t *panel_ptr /* host [P+1] */,
+                     uint32_t *brick_cols /* host [4 nb] */, uint64_t *brick_mask /* host [nb] */,
+                     uint32_t *brick_valptr /* host [nb+1] */, float *vals /* host [nnz] */);
+
+/* ---------------------------------------------------------------------------
+ * Routing and load balancing (Section 5).  Both setters drop cached work lists.
+ *
+ * spmm_plan_set_route: which kernel handles which panel (enum spmm_route).
+ * spmm_plan_set_split: how heavy panels are split along K into virtual panels:
+ *   parts = 0  Eq. 6-7: parts_p = ceil( blocks_p / avg_blocks / num_waves ),
+ *              num_waves = ceil(work items / (CUs * resident waves per CU))
+ *   parts = 1  never split
+ *   parts > 1  split every panel that has at least `parts` blocks into `parts`
+ *              (for tests of the merge path)
+ * Partial tiles of a split panel go to a plan-owned workspace and are summed in
+ * part order by a merge kernel, so results stay deterministic (the paper merges
+ * with atomics).
+ */
+int spmm_plan_set_route(spmm_plan_t *plan, int route);
+int spmm_plan_set_split(spmm_plan_t *plan, int parts);
+
+/* Host-only arithmetic of Eq. 6-7; needs no GPU.
+ *   n_panels, nbricks[n_panels]  bricks per panel (a block is 4 bricks)
+ *   work_items   thread-block count before splitting ("Total_thread_blocks")
+ *   num_cus, resident_per_cu     device capacity for one wave of work
+ *   parts_out[n_panels]          virtual panels per panel (>= 1)
+ *   waves_out                    num_waves (may be NULL)
+ */
+int spmm_partition_counts(int64_t n_panels, const uint32_t *nbricks /* host */, int64_t work_items,
+                          int32_t num_cus, int32_t resident_per_cu,
+                          uint32_t *parts_out /* host */, int64_t *waves_out /* host */);
+
+/* Work list that spmm_exec would use for N (builds and caches it).
+ * Items are (panel, brick_begin, brick_end, part, nparts); brick indices are
+ * global (into brick_mask).  Call with items = NULL to get the counts only. */
+typedef struct spmm_work_item {
+  uint32_t panel, brick_begin, brick_end, part, nparts;
+} spmm_work_item_t;
+
+typedef struct spmm_worklist_info {
+  int64_t n_mfma_items;   /* work items of the MFMA kernel                   */
+  int64_t n_valu_panels;  /* panels handled by the vector-ALU kernel          */
+  int64_t n_split_panels; /* panels split into more than one part             */
+  int64_t num_waves;      /* Eq. 7 denominator actually used                  */
+  int32_t n_tile;         /* columns of C per wavefront (16, 32, 64 or 128)   */
+  int32_t n_tiles;        /* ceil(N / n_tile)                                 */
+} spmm_worklist_info_t;
+
+int spmm_plan_worklist(spmm_plan_t *plan, int64_t N, spmm_worklist_info_t *info /* host */,
+                       spmm_work_item_t *items /* host [n_mfma_items] or NULL */,
+                       uint32_t *valu_panels /* host [n_valu_panels] or NULL */);
+
+void spmm_plan_destroy(spmm_plan_t *plan); /* NULL is allowed */
+
+const char *spmm_last_error(void); /* thread-local, valid until the next failing call */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPMM_H_ */

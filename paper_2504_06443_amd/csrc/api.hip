@@ -1,0 +1,540 @@
+// C ABI of libspmm_brick: plan construction (drives the kernels of
+// plan_kernels.hip), work-list building with the load balancer of paper
+// Section 5 (Eq. 6-7), kernel dispatch, the synergy model of Section 4 /
+// Table 1, and export accessors.
+#include "../../include/spmm.h"
+#include "spmm_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <vector>
+
+using namespace spmm;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) {                                                             \
+      status = fail(e_ == hipErrorOutOfMemory ? SPMM_ENOMEM : SPMM_EHIP, "%s: %s", #expr, \
+                    hipGetErrorString(e_));                                             \
+      goto done;                                                                        \
+    }                                                                                   \
+  } while (0)
+
+constexpr double kHbmBytesPerS = 8.0e12;    // MI355X published HBM3E bandwidth
+constexpr double kMfmaFp32Flops = 157.3e12; // MI355X published dense fp32 matrix peak
+
+struct WorkList {
+  int64_t N = 0;
+  spmm_worklist_info_t info{};
+  std::vector<spmm_work_item_t> h_items;   // exported form
+  std::vector<uint32_t> h_valu_panels;
+  WorkItem* d_items = nullptr;
+  uint32_t* d_valu_panels = nullptr;
+  MergeItem* d_merge = nullptr;
+  int64_t n_merge = 0;
+  int64_t n_slots = 0;
+  float* d_partial = nullptr;               // n_slots tiles of 16 x N
+  ~WorkList() {
+    if (d_items) (void)hipFree(d_items);
+    if (d_valu_panels) (void)hipFree(d_valu_panels);
+    if (d_merge) (void)hipFree(d_merge);
+    if (d_partial) (void)hipFree(d_partial);
+  }
+};
+
+}  // namespace
+
+struct spmm_plan {
+  int64_t M = 0, K = 0, nnz = 0, P = 0, nb = 0;
+  int device = 0;
+  int num_cus = 1;
+  // brick format (device)
+  uint32_t* panel_ptr = nullptr;
+  uint32_t* brick_cols = nullptr;
+  uint64_t* brick_mask = nullptr;
+  uint32_t* brick_valptr = nullptr;
+  float* vals = nullptr;          // nnz + 1
+  // plan-owned CSR copy for the vector-ALU kernel (device)
+  int32_t* rowptr = nullptr;
+  int32_t* colind = nullptr;
+  float* csr_vals = nullptr;
+  // host copies used by the work-list builder and the synergy model
+  std::vector<uint32_t> h_panel_ptr;
+  std::vector<uint8_t> h_panel_class;
+  unsigned long long h_counters[kNumCounters] = {};
+  int64_t n_active_cols = 0;
+  int route = SPMM_ROUTE_AUTO;
+  int split = 0;
+  std::map<int64_t, WorkList*> lists;
+
+  void drop_lists() {
+    for (auto& kv : lists) delete kv.second;
+    lists.clear();
+  }
+  ~spmm_plan() {
+    drop_lists();
+    void* bufs[] = {panel_ptr, brick_cols, brick_mask, brick_valptr, vals, rowptr, colind, csr_vals};
+    for (void* b : bufs)
+      if (b) (void)hipFree(b);
+  }
+};
+
+namespace {
+
+template <typename T>
+hipError_t dev_alloc(T** p, int64_t n) {
+  return hipMalloc((void**)p, (size_t)std::max<int64_t>(n, 1) * sizeof(T));
+}
+
+int classify(int64_t nnz, int64_t nb) {
+  if (nb == 0) return SPMM_NONE;
+  if (nnz < 8 * nb) return SPMM_LOW;
+  if (nnz < 16 * nb) return SPMM_MEDIUM;
+  return SPMM_HIGH;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Eq. 6-7 in integers: parts_p = max(1, ceil(blocks_p * P / (total_blocks * waves))).
+void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, int64_t capacity,
+                      uint32_t* parts, int64_t* waves_out) {
+  int64_t total = 0;
+  for (int64_t p = 0; p < P; ++p) total += ceil_div(nbricks[p], kBrickK);
+  const int64_t waves = std::max<int64_t>(1, ceil_div(work_items, std::max<int64_t>(1, capacity)));
+  for (int64_t p = 0; p < P; ++p) {
+    const int64_t blocks = ceil_div(nbricks[p], kBrickK);
+    int64_t q = 1;
+    if (total > 0 && blocks > 0) {
+      // blocks * P can exceed 2^63 only for absurd sizes; use 128-bit to be safe
+      const __int128 num = (__int128)blocks * P;
+      const __int128 den = (__int128)total * waves;
+      q = (int64_t)((num + den - 1) / den);
+    }
+    parts[p] = (uint32_t)std::max<int64_t>(1, q);
+  }
+  if (waves_out) *waves_out = waves;
+}
+
+// Builds (and uploads) the work list for N.  Synchronises the stream once.
+int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** out) {
+  auto found = pl->lists.find(N);
+  if (found != pl->lists.end()) {
+    *out = found->second;
+    return SPMM_OK;
+  }
+  int status = SPMM_OK;
+  WorkList* wl = new (std::nothrow) WorkList();
+  if (!wl) return fail(SPMM_ENOMEM, "host allocation failed");
+  wl->N = N;
+  const int tile = mfma_tile_for(std::max<int64_t>(N, 1));
+  const int V = tile >= 64 ? 4 : tile / 16;
+  wl->info.n_tile = tile;
+  wl->info.n_tiles = (int32_t)ceil_div(std::max<int64_t>(N, 1), tile);
+
+  // routing: which panels go to the MFMA kernel
+  std::vector<uint32_t> mfma_panels;
+  std::vector<uint32_t> nbricks;
+  for (int64_t p = 0; p < pl->P; ++p) {
+    const uint8_t cls = pl->h_panel_class[p];
+    bool to_mfma;
+    if (cls == 255) to_mfma = false;  // empty panel: the CSR kernel stores its zero rows
+    else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
+    else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
+    else to_mfma = cls != SPMM_LOW;
+    if (to_mfma) {
+      mfma_panels.push_back((uint32_t)p);
+      nbricks.push_back(pl->h_panel_ptr[p + 1] - pl->h_panel_ptr[p]);
+    } else {
+      wl->h_valu_panels.push_back((uint32_t)p);
+    }
+  }
+
+  // load balancing over the MFMA panels
+  const int64_t nm = (int64_t)mfma_panels.size();
+  std::vector<uint32_t> parts((size_t)nm, 1u);
+  int64_t waves = 1;
+  if (nm > 0) {
+    if (pl->split == 0) {
+      const int resident = mfma_resident_waves_per_cu(tile, N % V == 0);
+      partition_counts(nm, nbricks.data(), nm * wl->info.n_tiles,
+                       (int64_t)pl->num_cus * resident, parts.data(), &waves);
+    } else if (pl->split > 1) {
+      for (int64_t i = 0; i < nm; ++i)
+        if (ceil_div(nbricks[i], kBrickK) >= pl->split) parts[i] = (uint32_t)pl->split;
+    }
+  }
+  wl->info.num_waves = waves;
+
+  std::vector<WorkItem> items;
+  std::vector<MergeItem> merges;
+  int64_t slots = 0;
+  for (int64_t i = 0; i < nm; ++i) {
+    const uint32_t p = mfma_panels[i];
+    const uint32_t b0 = pl->h_panel_ptr[p];
+    const int64_t nbp = nbricks[i];
+    const int64_t blocks = ceil_div(nbp, kBrickK);
+    const int64_t want = std::min<int64_t>(parts[i], blocks);
+    const int64_t per = ceil_div(blocks, want);          // blocks per part
+    const int64_t nparts = ceil_div(blocks, per);        // parts that are not empty
+    if (nparts <= 1) {
+      items.push_back(WorkItem{p, b0, b0 + (uint32_t)nbp, kNoSlot});
+      wl->h_items.push_back(spmm_work_item_t{p, b0, b0 + (uint32_t)nbp, 0, 1});
+      continue;
+    }
+    merges.push_back(MergeItem{p, (uint32_t)slots, (uint32_t)nparts});
+    for (int64_t q = 0; q < nparts; ++q) {
+      const int64_t lo = std::min<int64_t>(nbp, q * per * kBrickK);
+      const int64_t hi = std::min<int64_t>(nbp, (q + 1) * per * kBrickK);
+      items.push_back(WorkItem{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)(slots + q)});
+      wl->h_items.push_back(
+          spmm_work_item_t{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)q, (uint32_t)nparts});
+    }
+    slots += nparts;
+  }
+  wl->info.n_mfma_items = (int64_t)items.size();
+  wl->info.n_valu_panels = (int64_t)wl->h_valu_panels.size();
+  wl->info.n_split_panels = (int64_t)merges.size();
+  wl->n_merge = (int64_t)merges.size();
+  wl->n_slots = slots;
+
+  HIP_TRY(dev_alloc(&wl->d_items, (int64_t)items.size()));
+  HIP_TRY(dev_alloc(&wl->d_valu_panels, (int64_t)wl->h_valu_panels.size()));
+  HIP_TRY(dev_alloc(&wl->d_merge, (int64_t)merges.size()));
+  if (slots > 0) HIP_TRY(dev_alloc(&wl->d_partial, slots * kPanel * std::max<int64_t>(N, 1)));
+  if (!items.empty())
+    HIP_TRY(hipMemcpyAsync(wl->d_items, items.data(), items.size() * sizeof(WorkItem),
+                           hipMemcpyHostToDevice, stream));
+  if (!wl->h_valu_panels.empty())
+    HIP_TRY(hipMemcpyAsync(wl->d_valu_panels, wl->h_valu_panels.data(),
+                           wl->h_valu_panels.size() * sizeof(uint32_t), hipMemcpyHostToDevice,
+                           stream));
+  if (!merges.empty())
+    HIP_TRY(hipMemcpyAsync(wl->d_merge, merges.data(), merges.size() * sizeof(MergeItem),
+                           hipMemcpyHostToDevice, stream));
+  HIP_TRY(hipStreamSynchronize(stream));  // the host vectors above go out of scope
+done:
+  if (status != SPMM_OK) {
+    delete wl;
+    return status;
+  }
+  pl->lists[N] = wl;
+  *out = wl;
+  return SPMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* spmm_last_error(void) { return g_err; }
+
+int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+              const float* vals, void* stream_, spmm_plan_t** out) {
+  if (!out) return fail(SPMM_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (M < 0 || K < 0 || nnz < 0) return fail(SPMM_EINVAL, "negative size");
+  if (!rowptr) return fail(SPMM_EINVAL, "rowptr is NULL");
+  if (nnz > 0 && (!colind || !vals)) return fail(SPMM_EINVAL, "colind/vals is NULL with nnz > 0");
+  if (nnz >= (int64_t(1) << 31) || M >= (int64_t(1) << 31) || K >= (int64_t(1) << 31))
+    return fail(SPMM_ELIMIT, "M, K and nnz must be below 2^31");
+
+  hipStream_t s = (hipStream_t)stream_;
+  int status = SPMM_OK;
+  spmm_plan_t* pl = new (std::nothrow) spmm_plan_t();
+  if (!pl) return fail(SPMM_ENOMEM, "host allocation failed");
+  const int64_t P = (M + kPanel - 1) / kPanel;
+  pl->M = M; pl->K = K; pl->nnz = nnz; pl->P = P;
+
+  // scratch (freed before returning)
+  uint32_t* d_err = nullptr;
+  uint32_t* ent_row = nullptr;
+  uint8_t* first = nullptr;
+  uint32_t* first_scan = nullptr;
+  uint32_t* scan_tmp = nullptr;
+  uint32_t* nbricks_p = nullptr;
+  uint32_t* panel_nnzptr = nullptr;
+  uint32_t* ent_brick = nullptr;
+  uint8_t* ent_bit = nullptr;
+  uint8_t* col_seen = nullptr;
+  uint8_t* panel_class = nullptr;
+  unsigned long long* counters = nullptr;
+  uint32_t h_err = 0, h_nb = 0, h_active = 0;
+
+  {
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&pl->device));
+    HIP_TRY(hipGetDeviceProperties(&prop, pl->device));
+    pl->num_cus = std::max(1, prop.multiProcessorCount);
+  }
+
+  // ---- validation (device), before anything trusts the indices
+  HIP_TRY(dev_alloc(&d_err, 1));
+  HIP_TRY(hipMemsetAsync(d_err, 0, sizeof(uint32_t), s));
+  HIP_TRY(launch_validate_rowptr(rowptr, M, nnz, d_err, s));
+  HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (h_err) {
+    status = fail(SPMM_EFORMAT, "invalid rowptr (%s)",
+                  (h_err & kErrRowptrEnds) ? "rowptr[0] != 0 or rowptr[M] != nnz" : "not monotone");
+    goto done;
+  }
+  HIP_TRY(dev_alloc(&ent_row, nnz));
+  HIP_TRY(launch_validate_cols(rowptr, colind, M, K, nnz, ent_row, d_err, s));
+  HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (h_err) {
+    status = fail(SPMM_EFORMAT, "invalid colind (%s)",
+                  (h_err & kErrColRange) ? "column out of range"
+                                         : "columns of a row not strictly ascending");
+    goto done;
+  }
+
+  // ---- a1: first occurrence of each column in its panel, scanned
+  HIP_TRY(dev_alloc(&first, nnz));
+  HIP_TRY(dev_alloc(&first_scan, nnz + 1));
+  HIP_TRY(dev_alloc(&scan_tmp, (int64_t)scan_tmp_elems(std::max(nnz, P + 1))));
+  HIP_TRY(launch_first_in_panel(rowptr, colind, ent_row, nnz, first, s));
+  HIP_TRY(launch_scan_u8(first, nnz, first_scan, scan_tmp, s));
+
+  // ---- a2: bricks per panel -> panel_ptr
+  HIP_TRY(dev_alloc(&nbricks_p, P));
+  HIP_TRY(dev_alloc(&panel_nnzptr, P + 1));
+  HIP_TRY(dev_alloc(&pl->panel_ptr, P + 1));
+  HIP_TRY(launch_panel_counts(rowptr, first_scan, M, P, nbricks_p, panel_nnzptr, s));
+  HIP_TRY(launch_scan_u32(nbricks_p, P, pl->panel_ptr, scan_tmp, s));
+  HIP_TRY(hipMemcpyAsync(&h_nb, pl->panel_ptr + P, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(&h_active, first_scan + nnz, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  pl->nb = h_nb;
+  pl->n_active_cols = h_active;
+  if ((int64_t)h_nb * kBrickK >= (int64_t(1) << 32)) {
+    status = fail(SPMM_ELIMIT, "4 * bricks must be below 2^32");
+    goto done;
+  }
+
+  // ---- a2/a3: brick columns and patterns
+  HIP_TRY(dev_alloc(&pl->brick_cols, pl->nb * kBrickK));
+  HIP_TRY(dev_alloc(&pl->brick_mask, pl->nb));
+  HIP_TRY(dev_alloc(&pl->brick_valptr, pl->nb + 1));
+  HIP_TRY(dev_alloc(&pl->vals, nnz + 1));
+  HIP_TRY(dev_alloc(&ent_brick, nnz));
+  HIP_TRY(dev_alloc(&ent_bit, nnz));
+  HIP_TRY(dev_alloc(&col_seen, K));
+  HIP_TRY(launch_fill_u32(pl->brick_cols, pl->nb * kBrickK, kPadCol, s));
+  HIP_TRY(launch_fill_u64(pl->brick_mask, pl->nb, 0ull, s));
+  HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
+  HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, sizeof(float), s));
+  HIP_TRY(launch_rank_scatter(rowptr, colind, ent_row, first, first_scan, pl->panel_ptr, M, nnz,
+                              pl->brick_cols, pl->brick_mask, ent_brick, ent_bit, col_seen, s));
+
+  // ---- a4: value offsets and packed values
+  if ((int64_t)scan_tmp_elems(pl->nb) > (int64_t)scan_tmp_elems(std::max(nnz, P + 1))) {
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipFree(scan_tmp));
+    scan_tmp = nullptr;
+    HIP_TRY(dev_alloc(&scan_tmp, (int64_t)scan_tmp_elems(pl->nb)));
+  }
+  HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
+  HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
+                             pl->vals, s));
+
+  // ---- a5: per-panel classes and the synergy counts
+  HIP_TRY(dev_alloc(&panel_class, P));
+  HIP_TRY(dev_alloc(&counters, kNumCounters));
+  HIP_TRY(hipMemsetAsync(counters, 0, kNumCounters * sizeof(unsigned long long), s));
+  HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
+  HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
+  HIP_TRY(launch_count_flags(col_seen, K, counters + kCntDistinctCols, s));
+
+  // ---- plan-owned CSR copy for the vector-ALU kernel
+  HIP_TRY(dev_alloc(&pl->rowptr, M + 1));
+  HIP_TRY(dev_alloc(&pl->colind, nnz));
+  HIP_TRY(dev_alloc(&pl->csr_vals, nnz));
+  HIP_TRY(hipMemcpyAsync(pl->rowptr, rowptr, (size_t)(M + 1) * sizeof(int32_t),
+                         hipMemcpyDeviceToDevice, s));
+  if (nnz > 0) {
+    HIP_TRY(hipMemcpyAsync(pl->colind, colind, (size_t)nnz * sizeof(int32_t),
+                           hipMemcpyDeviceToDevice, s));
+    HIP_TRY(hipMemcpyAsync(pl->csr_vals, vals, (size_t)nnz * sizeof(float),
+                           hipMemcpyDeviceToDevice, s));
+  }
+
+  // ---- host copies for the work-list builder and the model
+  try {
+    pl->h_panel_ptr.resize((size_t)P + 1);
+    pl->h_panel_class.resize((size_t)std::max<int64_t>(P, 1));
+  } catch (const std::bad_alloc&) {
+    status = fail(SPMM_ENOMEM, "host allocation failed");
+    goto done;
+  }
+  HIP_TRY(hipMemcpyAsync(pl->h_panel_ptr.data(), pl->panel_ptr, (size_t)(P + 1) * sizeof(uint32_t),
+                         hipMemcpyDeviceToHost, s));
+  if (P > 0)
+    HIP_TRY(hipMemcpyAsync(pl->h_panel_class.data(), panel_class, (size_t)P,
+                           hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(pl->h_counters, counters, kNumCounters * sizeof(unsigned long long),
+                         hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+
+done:
+  if (status != SPMM_OK) (void)hipStreamSynchronize(s);
+  {
+    void* scratch[] = {d_err, ent_row, first, first_scan, scan_tmp, nbricks_p, panel_nnzptr,
+                       ent_brick, ent_bit, col_seen, panel_class, counters};
+    for (void* b : scratch)
+      if (b) (void)hipFree(b);
+  }
+  if (status != SPMM_OK) {
+    delete pl;
+    return status;
+  }
+  *out = pl;
+  return SPMM_OK;
+}
+
+int spmm_exec(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream_) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (N < 0) return fail(SPMM_EINVAL, "N is negative");
+  if (N == 0 || pl->M == 0) return SPMM_OK;
+  if (!C) return fail(SPMM_EINVAL, "C is NULL");
+  if (!B && pl->K > 0) return fail(SPMM_EINVAL, "B is NULL");
+  hipStream_t s = (hipStream_t)stream_;
+  WorkList* wl = nullptr;
+  int status = build_worklist(pl, N, s, &wl);
+  if (status != SPMM_OK) return status;
+  const BrickFormat f{pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals};
+  HIP_TRY(launch_spmm_mfma(f, wl->d_items, wl->info.n_mfma_items, B, C, wl->d_partial, pl->M, N, s));
+  HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, wl->d_valu_panels,
+                           wl->info.n_valu_panels, B, C, pl->M, N, s));
+  HIP_TRY(launch_merge(wl->d_merge, wl->n_merge, wl->d_partial, C, pl->M, N, s));
+done:
+  return status;
+}
+
+int spmm_synergy(const spmm_plan_t* pl, int64_t N, spmm_synergy_t* o) {
+  if (!pl || !o) return fail(SPMM_EINVAL, "NULL argument");
+  if (N < 0) return fail(SPMM_EINVAL, "N is negative");
+  memset(o, 0, sizeof(*o));
+  o->M = pl->M; o->K = pl->K; o->nnz = pl->nnz;
+  o->n_panels = pl->P;
+  o->n_nonempty_panels = (int64_t)pl->h_counters[kCntNonEmptyPanels];
+  o->n_bricks = pl->nb;
+  o->n_active_cols = pl->n_active_cols;
+  o->n_distinct_cols = (int64_t)pl->h_counters[kCntDistinctCols];
+  for (int c = 0; c < 3; ++c) {
+    o->panels_by_class[c] = (int64_t)pl->h_counters[kCntPanelsByClass + c];
+    o->bricks_by_class[c] = (int64_t)pl->h_counters[kCntBricksByClass + c];
+    o->nnz_by_class[c] = (int64_t)pl->h_counters[kCntNnzByClass + c];
+  }
+  for (int k = 0; k < 65; ++k) o->brick_pop_hist[k] = (int64_t)pl->h_counters[kCntPopHist + k];
+  o->synergy_class = classify(pl->nnz, pl->nb);
+  const double nnz = (double)pl->nnz, nb = (double)pl->nb, n = (double)N;
+  o->alpha_brick = pl->nb ? nnz / (64.0 * nb) : 0.0;
+  o->alpha_col = pl->n_active_cols ? nnz / (16.0 * (double)pl->n_active_cols) : 0.0;
+  o->beta = 1.0;
+  o->oi_shmem = 512.0 * o->alpha_brick * o->beta;
+  const double a_bytes = 4.0 * nnz + 28.0 * nb + 4.0 + 4.0 * (double)(pl->P + 1);
+  o->bytes_min = a_bytes + 4.0 * n * (double)o->n_distinct_cols + 4.0 * n * (double)pl->M;
+  o->bytes_noreuse = a_bytes + 4.0 * n * (double)o->n_active_cols + 4.0 * n * (double)pl->M;
+  const double flops = 2.0 * nnz * n;
+  o->oi_hbm_min = flops / o->bytes_min;
+  o->oi_hbm_noreuse = flops / o->bytes_noreuse;
+  o->roof_gflops_hbm = o->oi_hbm_min * kHbmBytesPerS * 1e-9;
+  o->roof_gflops_mfma = o->alpha_brick * kMfmaFp32Flops * 1e-9;
+  return SPMM_OK;
+}
+
+int spmm_plan_sizes(const spmm_plan_t* pl, spmm_sizes_t* o) {
+  if (!pl || !o) return fail(SPMM_EINVAL, "NULL argument");
+  o->M = pl->M; o->K = pl->K; o->nnz = pl->nnz; o->n_panels = pl->P; o->n_bricks = pl->nb;
+  return SPMM_OK;
+}
+
+int spmm_plan_export(const spmm_plan_t* pl, uint32_t* panel_ptr, uint32_t* brick_cols,
+                     uint64_t* brick_mask, uint32_t* brick_valptr, float* vals) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  int status = SPMM_OK;
+  HIP_TRY(hipDeviceSynchronize());
+  if (panel_ptr)
+    HIP_TRY(hipMemcpy(panel_ptr, pl->panel_ptr, (size_t)(pl->P + 1) * 4, hipMemcpyDeviceToHost));
+  if (brick_cols && pl->nb)
+    HIP_TRY(hipMemcpy(brick_cols, pl->brick_cols, (size_t)pl->nb * 16, hipMemcpyDeviceToHost));
+  if (brick_mask && pl->nb)
+    HIP_TRY(hipMemcpy(brick_mask, pl->brick_mask, (size_t)pl->nb * 8, hipMemcpyDeviceToHost));
+  if (brick_valptr)
+    HIP_TRY(hipMemcpy(brick_valptr, pl->brick_valptr, (size_t)(pl->nb + 1) * 4,
+                      hipMemcpyDeviceToHost));
+  if (vals && pl->nnz)
+    HIP_TRY(hipMemcpy(vals, pl->vals, (size_t)pl->nnz * 4, hipMemcpyDeviceToHost));
+done:
+  return status;
+}
+
+int spmm_plan_set_route(spmm_plan_t* pl, int route) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (route < SPMM_ROUTE_AUTO || route > SPMM_ROUTE_VALU) return fail(SPMM_EINVAL, "bad route");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
+  pl->route = route;
+  pl->drop_lists();
+  return SPMM_OK;
+}
+
+int spmm_plan_set_split(spmm_plan_t* pl, int parts) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (parts < 0) return fail(SPMM_EINVAL, "parts is negative");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
+  pl->split = parts;
+  pl->drop_lists();
+  return SPMM_OK;
+}
+
+int spmm_partition_counts(int64_t n_panels, const uint32_t* nbricks, int64_t work_items,
+                          int32_t num_cus, int32_t resident_per_cu, uint32_t* parts_out,
+                          int64_t* waves_out) {
+  if (n_panels < 0 || work_items < 0 || num_cus < 1 || resident_per_cu < 1)
+    return fail(SPMM_EINVAL, "bad argument");
+  if (n_panels > 0 && (!nbricks || !parts_out)) return fail(SPMM_EINVAL, "NULL argument");
+  partition_counts(n_panels, nbricks, work_items, (int64_t)num_cus * resident_per_cu, parts_out,
+                   waves_out);
+  return SPMM_OK;
+}
+
+int spmm_plan_worklist(spmm_plan_t* pl, int64_t N, spmm_worklist_info_t* info,
+                       spmm_work_item_t* items, uint32_t* valu_panels) {
+  if (!pl || !info) return fail(SPMM_EINVAL, "NULL argument");
+  if (N < 1) return fail(SPMM_EINVAL, "N must be positive");
+  WorkList* wl = nullptr;
+  const int status = build_worklist(pl, N, nullptr, &wl);
+  if (status != SPMM_OK) return status;
+  *info = wl->info;
+  if (items && !wl->h_items.empty())
+    memcpy(items, wl->h_items.data(), wl->h_items.size() * sizeof(spmm_work_item_t));
+  if (valu_panels && !wl->h_valu_panels.empty())
+    memcpy(valu_panels, wl->h_valu_panels.data(), wl->h_valu_panels.size() * sizeof(uint32_t));
+  return SPMM_OK;
+}
+
+void spmm_plan_destroy(spmm_plan_t* pl) {
+  if (!pl) return;
+  (void)hipDeviceSynchronize();
+  delete pl;
+}
+
+}  // extern "C"

@@ -1,0 +1,416 @@
+// CSR -> brick format on the GPU (paper Section 3.2: active-column compaction,
+// bricks of 4 columns, 64-bit pattern per brick, values packed row-major).
+//
+// All kernels are one-thread-per-entry (or per row / panel / brick) and use no
+// inter-workgroup waiting; the only atomics are integer OR / ADD, so every
+// output is reproducible bit for bit.
+//
+// The census of active columns avoids sorting: the rows of a panel are already
+// sorted, so "is this the first row of the panel that holds column j" and
+// "how many distinct columns of the panel are smaller than j" are answered by
+// binary searches in the (at most 16) rows of the panel plus one exclusive scan
+// of the first-occurrence flags over the whole entry array.
+#include "spmm_internal.h"
+
+#include <algorithm>
+
+namespace spmm {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline unsigned grid_for(int64_t n, int threads = kThreads) {
+  int64_t g = (n + threads - 1) / threads;
+  return (unsigned)(g > 0 ? g : 1);
+}
+
+// first index in [lo, hi) whose column is >= j
+__device__ inline int64_t lower_bound_col(const int32_t* __restrict__ colind, int64_t lo,
+                                          int64_t hi, int32_t j) {
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (colind[mid] < j) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// ---------------------------------------------------------------- validation
+__global__ void k_validate_rowptr(const int32_t* __restrict__ rowptr, int64_t M, int64_t nnz,
+                                  uint32_t* err) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i > M) return;
+  uint32_t e = 0;
+  const int64_t a = rowptr[i];
+  if (i == 0 && a != 0) e |= kErrRowptrEnds;
+  if (i == M && a != nnz) e |= kErrRowptrEnds;
+  if (a < 0 || a > nnz) e |= kErrRowptrOrder;
+  if (i < M) {
+    const int64_t b = rowptr[i + 1];
+    if (b < a) e |= kErrRowptrOrder;
+  }
+  if (e) atomicOr(err, e);
+}
+
+// Requires a valid rowptr.  Also records the row of every entry.
+__global__ void k_validate_cols(const int32_t* __restrict__ rowptr,
+                                const int32_t* __restrict__ colind, int64_t M, int64_t K,
+                                int64_t nnz, uint32_t* __restrict__ ent_row, uint32_t* err) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  int64_t lo = 0, hi = M;  // rowptr[lo] <= e < rowptr[hi]
+  while (hi - lo > 1) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (rowptr[mid] <= e) lo = mid; else hi = mid;
+  }
+  ent_row[e] = (uint32_t)lo;
+  const int64_t j = colind[e];
+  uint32_t bad = 0;
+  if (j < 0 || j >= K) bad |= kErrColRange;
+  if (e > rowptr[lo] && colind[e - 1] >= j) bad |= kErrColOrder;
+  if (bad) atomicOr(err, bad);
+}
+
+// ---------------------------------------------------------------- a1 census
+// first[e] = 1 iff no earlier row of the same panel stores column colind[e].
+__global__ void k_first_in_panel(const int32_t* __restrict__ rowptr,
+                                 const int32_t* __restrict__ colind,
+                                 const uint32_t* __restrict__ ent_row, int64_t nnz,
+                                 uint8_t* __restrict__ first) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  const int64_t i = ent_row[e];
+  const int32_t j = colind[e];
+  const int64_t r0 = i & ~(int64_t)(kPanel - 1);
+  uint8_t f = 1;
+  for (int64_t r = r0; r < i; ++r) {
+    const int64_t s = rowptr[r], t = rowptr[r + 1];
+    const int64_t pos = lower_bound_col(colind, s, t, j);
+    if (pos < t && colind[pos] == j) { f = 0; break; }
+  }
+  first[e] = f;
+}
+
+// a2: bricks per panel and the entry offset of each panel.
+__global__ void k_panel_counts(const int32_t* __restrict__ rowptr,
+                               const uint32_t* __restrict__ first_scan, int64_t M, int64_t P,
+                               uint32_t* __restrict__ nbricks_p,
+                               uint32_t* __restrict__ panel_nnzptr) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p > P) return;
+  const int64_t r0 = min(p * kPanel, M);
+  const int64_t e0 = rowptr[r0];
+  panel_nnzptr[p] = (uint32_t)e0;
+  if (p < P) {
+    const int64_t r1 = min(r0 + kPanel, M);
+    const uint32_t ncols = first_scan[rowptr[r1]] - first_scan[e0];
+    nbricks_p[p] = (ncols + kBrickK - 1) / kBrickK;
+  }
+}
+
+template <typename T>
+__global__ void k_fill(T* __restrict__ p, int64_t n, T v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// a2 + a3: rank of the entry's column among the panel's active columns, then
+// brick id, brick column and pattern bit 4*row + column.
+__global__ void k_rank_scatter(const int32_t* __restrict__ rowptr,
+                               const int32_t* __restrict__ colind,
+                               const uint32_t* __restrict__ ent_row,
+                               const uint8_t* __restrict__ first,
+                               const uint32_t* __restrict__ first_scan,
+                               const uint32_t* __restrict__ panel_ptr, int64_t M, int64_t nnz,
+                               uint32_t* __restrict__ brick_cols, uint64_t* brick_mask,
+                               uint32_t* __restrict__ ent_brick, uint8_t* __restrict__ ent_bit,
+                               uint8_t* __restrict__ col_seen) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  const int64_t i = ent_row[e];
+  const int32_t j = colind[e];
+  const int64_t p = i / kPanel;
+  const int64_t r0 = p * kPanel, r1 = min(r0 + kPanel, M);
+  uint32_t rank = 0;
+  for (int64_t r = r0; r < r1; ++r) {
+    const int64_t s = rowptr[r], t = rowptr[r + 1];
+    const int64_t pos = (r == i) ? e : lower_bound_col(colind, s, t, j);
+    rank += first_scan[pos] - first_scan[s];
+  }
+  const uint32_t b = panel_ptr[p] + rank / kBrickK;
+  const uint32_t c = rank % kBrickK;
+  const uint32_t bit = (uint32_t)(i - r0) * kBrickK + c;
+  atomicOr((unsigned long long*)&brick_mask[b], 1ull << bit);
+  if (first[e]) brick_cols[(int64_t)b * kBrickK + c] = (uint32_t)j;
+  ent_brick[e] = b;
+  ent_bit[e] = (uint8_t)bit;
+  col_seen[j] = 1;
+}
+
+// a4: position of a value = start of its brick + set bits below its own bit.
+__global__ void k_pack_values(const float* __restrict__ vals,
+                              const uint32_t* __restrict__ ent_brick,
+                              const uint8_t* __restrict__ ent_bit,
+                              const uint64_t* __restrict__ brick_mask,
+                              const uint32_t* __restrict__ brick_valptr, int64_t nnz,
+                              float* __restrict__ packed) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  const uint32_t b = ent_brick[e];
+  const uint64_t below = brick_mask[b] & ((1ull << ent_bit[e]) - 1ull);
+  packed[(int64_t)brick_valptr[b] + __popcll(below)] = vals[e];
+}
+
+// a5: per-panel class (Table 1, integer compare) and class totals.
+__global__ void k_panel_classes(const uint32_t* __restrict__ panel_ptr,
+                                const uint32_t* __restrict__ panel_nnzptr, int64_t P,
+                                uint8_t* __restrict__ panel_class, unsigned long long* counters) {
+  __shared__ unsigned long long acc[10];
+  if (threadIdx.x < 10) acc[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < P) {
+    const unsigned long long nb = panel_ptr[p + 1] - panel_ptr[p];
+    const unsigned long long nz = panel_nnzptr[p + 1] - panel_nnzptr[p];
+    uint8_t cls = 255;
+    if (nb) {
+      cls = nz < 8 * nb ? 0 : (nz < 16 * nb ? 1 : 2);
+      atomicAdd(&acc[kCntPanelsByClass + cls], 1ull);
+      atomicAdd(&acc[kCntBricksByClass + cls], nb);
+      atomicAdd(&acc[kCntNnzByClass + cls], nz);
+      atomicAdd(&acc[kCntNonEmptyPanels], 1ull);
+    }
+    panel_class[p] = cls;
+  }
+  __syncthreads();
+  if (threadIdx.x < 10 && acc[threadIdx.x]) atomicAdd(&counters[threadIdx.x], acc[threadIdx.x]);
+}
+
+__global__ void k_brick_hist(const uint64_t* __restrict__ brick_mask, int64_t nb,
+                             unsigned long long* counters) {
+  __shared__ unsigned int h[65];
+  for (int t = threadIdx.x; t < 65; t += blockDim.x) h[t] = 0;
+  __syncthreads();
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < nb; b += stride)
+    atomicAdd(&h[__popcll(brick_mask[b])], 1u);
+  __syncthreads();
+  for (int t = threadIdx.x; t < 65; t += blockDim.x)
+    if (h[t]) atomicAdd(&counters[kCntPopHist + t], (unsigned long long)h[t]);
+}
+
+__global__ void k_count_flags(const uint8_t* __restrict__ flags, int64_t n,
+                              unsigned long long* counter) {
+  __shared__ unsigned int total;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  unsigned int mine = 0;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    mine += flags[i];
+  if (mine) atomicAdd(&total, mine);
+  __syncthreads();
+  if (threadIdx.x == 0 && total) atomicAdd(counter, (unsigned long long)total);
+}
+
+// ---------------------------------------------------------------- scan
+// Three-pass exclusive scan (block sums, scan of block sums, rescan + offset).
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 16;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+struct LoadU8 { const uint8_t* p; __device__ uint32_t operator()(int64_t i) const { return p[i]; } };
+struct LoadU32 { const uint32_t* p; __device__ uint32_t operator()(int64_t i) const { return p[i]; } };
+struct LoadPopc { const uint64_t* p; __device__ uint32_t operator()(int64_t i) const { return __popcll(p[i]); } };
+
+// exclusive scan of one value per thread across the block; returns the block total
+__device__ inline uint32_t block_exclusive(uint32_t v, uint32_t* total_out) {
+  __shared__ uint32_t wave_sum[kScanThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += up;
+  }
+  __syncthreads();  // protect wave_sum from the previous use
+  if (lane == 63) wave_sum[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kScanThreads / 64; ++w) {
+    if (w < wave) base += wave_sum[w];
+    total += wave_sum[w];
+  }
+  *total_out = total;
+  return base + incl - v;
+}
+
+template <typename Load>
+__global__ void k_scan_block_sums(Load load, int64_t n, uint32_t* __restrict__ block_sums) {
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  uint32_t s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k)
+    if (base + k < n) s += load(base + k);
+  uint32_t total;
+  block_exclusive(s, &total);
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+// single block: in-place exclusive scan of block_sums[0..nblocks), total to *grand
+__global__ void k_scan_of_sums(uint32_t* __restrict__ block_sums, int64_t nblocks,
+                               uint32_t* __restrict__ grand) {
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < nblocks; base += kScanThreads) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < nblocks ? block_sums[i] : 0;
+    uint32_t total;
+    const uint32_t ex = block_exclusive(v, &total);
+    if (i < nblocks) block_sums[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) *grand = carry;
+}
+
+template <typename Load>
+__global__ void k_scan_final(Load load, int64_t n, const uint32_t* __restrict__ block_offsets,
+                             uint32_t* __restrict__ out) {
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  uint32_t v[kScanItems];
+  uint32_t s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) {
+    v[k] = base + k < n ? load(base + k) : 0;
+    s += v[k];
+  }
+  uint32_t total;
+  uint32_t run = block_offsets[blockIdx.x] + block_exclusive(s, &total);
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) {
+    if (base + k < n) out[base + k] = run;
+    run += v[k];
+  }
+}
+
+template <typename Load>
+hipError_t scan_impl(Load load, int64_t n, uint32_t* out, uint32_t* tmp, hipStream_t s) {
+  // out[n] receives the total even when n == 0
+  const int64_t nblocks = (n + kScanTile - 1) / kScanTile;
+  if (nblocks > 0)
+    hipLaunchKernelGGL(k_scan_block_sums<Load>, dim3((unsigned)nblocks), dim3(kScanThreads), 0, s,
+                       load, n, tmp);
+  hipLaunchKernelGGL(k_scan_of_sums, dim3(1), dim3(kScanThreads), 0, s, tmp, nblocks, out + n);
+  if (nblocks > 0)
+    hipLaunchKernelGGL(k_scan_final<Load>, dim3((unsigned)nblocks), dim3(kScanThreads), 0, s, load,
+                       n, tmp, out);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t scan_tmp_elems(int64_t n) { return (size_t)((n + kScanTile - 1) / kScanTile) + 1; }
+
+hipError_t launch_scan_u8(const uint8_t* in, int64_t n, uint32_t* out, uint32_t* tmp, hipStream_t s) {
+  return scan_impl(LoadU8{in}, n, out, tmp, s);
+}
+hipError_t launch_scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
+                           hipStream_t s) {
+  return scan_impl(LoadU32{in}, n, out, tmp, s);
+}
+hipError_t launch_scan_popc64(const uint64_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
+                              hipStream_t s) {
+  return scan_impl(LoadPopc{in}, n, out, tmp, s);
+}
+
+hipError_t launch_validate_rowptr(const int32_t* rowptr, int64_t M, int64_t nnz, uint32_t* err,
+                                  hipStream_t s) {
+  hipLaunchKernelGGL(k_validate_rowptr, dim3(grid_for(M + 1)), dim3(kThreads), 0, s, rowptr, M, nnz,
+                     err);
+  return hipGetLastError();
+}
+
+hipError_t launch_validate_cols(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t K,
+                                int64_t nnz, uint32_t* ent_row, uint32_t* err, hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_validate_cols, dim3(grid_for(nnz)), dim3(kThreads), 0, s, rowptr, colind, M,
+                     K, nnz, ent_row, err);
+  return hipGetLastError();
+}
+
+hipError_t launch_first_in_panel(const int32_t* rowptr, const int32_t* colind,
+                                 const uint32_t* ent_row, int64_t nnz, uint8_t* first,
+                                 hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_first_in_panel, dim3(grid_for(nnz)), dim3(kThreads), 0, s, rowptr, colind,
+                     ent_row, nnz, first);
+  return hipGetLastError();
+}
+
+hipError_t launch_panel_counts(const int32_t* rowptr, const uint32_t* first_scan, int64_t M,
+                               int64_t P, uint32_t* nbricks_p, uint32_t* panel_nnzptr,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(k_panel_counts, dim3(grid_for(P + 1)), dim3(kThreads), 0, s, rowptr,
+                     first_scan, M, P, nbricks_p, panel_nnzptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_fill<uint32_t>, dim3(grid_for(n)), dim3(kThreads), 0, s, p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_fill<uint64_t>, dim3(grid_for(n)), dim3(kThreads), 0, s, p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t launch_rank_scatter(const int32_t* rowptr, const int32_t* colind,
+                               const uint32_t* ent_row, const uint8_t* first,
+                               const uint32_t* first_scan, const uint32_t* panel_ptr, int64_t M,
+                               int64_t nnz, uint32_t* brick_cols, uint64_t* brick_mask,
+                               uint32_t* ent_brick, uint8_t* ent_bit, uint8_t* col_seen,
+                               hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_rank_scatter, dim3(grid_for(nnz)), dim3(kThreads), 0, s, rowptr, colind,
+                     ent_row, first, first_scan, panel_ptr, M, nnz, brick_cols, brick_mask,
+                     ent_brick, ent_bit, col_seen);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_values(const float* vals, const uint32_t* ent_brick, const uint8_t* ent_bit,
+                              const uint64_t* brick_mask, const uint32_t* brick_valptr,
+                              int64_t nnz, float* packed, hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_pack_values, dim3(grid_for(nnz)), dim3(kThreads), 0, s, vals, ent_brick,
+                     ent_bit, brick_mask, brick_valptr, nnz, packed);
+  return hipGetLastError();
+}
+
+hipError_t launch_panel_classes(const uint32_t* panel_ptr, const uint32_t* panel_nnzptr, int64_t P,
+                                uint8_t* panel_class, unsigned long long* counters, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_panel_classes, dim3(grid_for(P)), dim3(kThreads), 0, s, panel_ptr,
+                     panel_nnzptr, P, panel_class, counters);
+  return hipGetLastError();
+}
+
+hipError_t launch_brick_hist(const uint64_t* brick_mask, int64_t nb, unsigned long long* counters,
+                             hipStream_t s) {
+  if (nb == 0) return hipSuccess;
+  const unsigned g = (unsigned)std::min<int64_t>(grid_for(nb), 2048);
+  hipLaunchKernelGGL(k_brick_hist, dim3(g), dim3(kThreads), 0, s, brick_mask, nb, counters);
+  return hipGetLastError();
+}
+
+hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long long* counter,
+                              hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const unsigned g = (unsigned)std::min<int64_t>(grid_for(n), 2048);
+  hipLaunchKernelGGL(k_count_flags, dim3(g), dim3(kThreads), 0, s, flags, n, counter);
+  return hipGetLastError();
+}
+
+}  // namespace spmm

@@ -1,0 +1,103 @@
+// Internal declarations shared by the HIP translation units of libspmm_brick.
+// Host-callable launchers only; every launcher enqueues on `s` and returns the
+// launch status.  All pointers are device pointers unless named h_*.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spmm {
+
+constexpr int kPanel = 16;            // TM: rows per row panel (Section 3.2)
+constexpr int kBrickK = 4;            // brick_k: columns per brick
+constexpr uint32_t kPadCol = 0xFFFFFFFFu;
+
+// error bits written by the validation kernels
+enum : uint32_t {
+  kErrRowptrEnds = 1u,      // rowptr[0] != 0 or rowptr[M] != nnz
+  kErrRowptrOrder = 2u,     // rowptr decreases or leaves [0, nnz]
+  kErrColRange = 4u,        // column outside [0, K)
+  kErrColOrder = 8u         // columns of a row not strictly ascending
+};
+
+// counters gathered at plan time (device array of kNumCounters u64)
+enum : int {
+  kCntPanelsByClass = 0,    // 3
+  kCntBricksByClass = 3,    // 3
+  kCntNnzByClass = 6,       // 3
+  kCntNonEmptyPanels = 9,
+  kCntDistinctCols = 10,
+  kCntPopHist = 11,         // 65
+  kNumCounters = 76
+};
+
+struct WorkItem {           // one wavefront's share of the MFMA kernel
+  uint32_t panel;
+  uint32_t brick_begin;     // global brick index
+  uint32_t brick_end;
+  uint32_t slot;            // kNoSlot: store to C; else index of a 16 x N partial tile
+};
+constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
+
+struct MergeItem {          // one split panel
+  uint32_t panel;
+  uint32_t slot_begin;      // its partial tiles are slot_begin .. slot_begin+nparts-1
+  uint32_t nparts;
+};
+
+// ---- plan (a1..a5) -------------------------------------------------------
+hipError_t launch_validate_rowptr(const int32_t* rowptr, int64_t M, int64_t nnz, uint32_t* err,
+                                  hipStream_t s);
+hipError_t launch_validate_cols(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t K,
+                                int64_t nnz, uint32_t* ent_row, uint32_t* err, hipStream_t s);
+hipError_t launch_first_in_panel(const int32_t* rowptr, const int32_t* colind,
+                                 const uint32_t* ent_row, int64_t nnz, uint8_t* first,
+                                 hipStream_t s);
+hipError_t launch_panel_counts(const int32_t* rowptr, const uint32_t* first_scan, int64_t M,
+                               int64_t P, uint32_t* nbricks_p, uint32_t* panel_nnzptr,
+                               hipStream_t s);
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
+hipError_t launch_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
+hipError_t launch_rank_scatter(const int32_t* rowptr, const int32_t* colind,
+                               const uint32_t* ent_row, const uint8_t* first,
+                               const uint32_t* first_scan, const uint32_t* panel_ptr, int64_t M,
+                               int64_t nnz, uint32_t* brick_cols, uint64_t* brick_mask,
+                               uint32_t* ent_brick, uint8_t* ent_bit, uint8_t* col_seen,
+                               hipStream_t s);
+hipError_t launch_pack_values(const float* vals, const uint32_t* ent_brick, const uint8_t* ent_bit,
+                              const uint64_t* brick_mask, const uint32_t* brick_valptr,
+                              int64_t nnz, float* packed, hipStream_t s);
+hipError_t launch_panel_classes(const uint32_t* panel_ptr, const uint32_t* panel_nnzptr, int64_t P,
+                                uint8_t* panel_class, unsigned long long* counters, hipStream_t s);
+hipError_t launch_brick_hist(const uint64_t* brick_mask, int64_t nb, unsigned long long* counters,
+                             hipStream_t s);
+hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long long* counter,
+                              hipStream_t s);
+
+// exclusive scans; out has n+1 entries (out[n] = total); tmp holds block sums
+size_t scan_tmp_elems(int64_t n);
+hipError_t launch_scan_u8(const uint8_t* in, int64_t n, uint32_t* out, uint32_t* tmp, hipStream_t s);
+hipError_t launch_scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
+                           hipStream_t s);
+hipError_t launch_scan_popc64(const uint64_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
+                              hipStream_t s);
+
+// ---- exec (a6..a8) -------------------------------------------------------
+struct BrickFormat {
+  const uint32_t* brick_cols;
+  const uint64_t* brick_mask;
+  const uint32_t* brick_valptr;
+  const float* vals;   // nnz + 1 floats (one pad element)
+};
+
+int mfma_tile_for(int64_t N);   // columns of C per wavefront: 16, 32, 64 or 128
+int mfma_resident_waves_per_cu(int n_tile, bool aligned);
+hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
+                            const float* B, float* C, float* partial, int64_t M, int64_t N,
+                            hipStream_t s);
+hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const float* vals,
+                            const uint32_t* panels, int64_t n_panels, const float* B, float* C,
+                            int64_t M, int64_t N, hipStream_t s);
+hipError_t launch_merge(const MergeItem* items, int64_t n_items, const float* partial, float* C,
+                        int64_t M, int64_t N, hipStream_t s);
+
+}  // namespace spmm

@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Format, masks and synergy counts bit-exact; C within
+1e-5 of sum|a.b| per element, and exactly zero where that sum is zero."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_06443_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+FMT_KEYS = ("panel_ptr", "brick_cols", "brick_mask", "brick_valptr", "vals")
+INT_KEYS = ("M", "K", "nnz", "n_panels", "n_nonempty_panels", "n_bricks", "n_active_cols",
+            "n_distinct_cols", "panels_by_class", "bricks_by_class", "nnz_by_class",
+            "brick_pop_hist", "synergy_class")
+FP_KEYS = ("alpha_brick", "alpha_col", "beta", "oi_shmem", "bytes_min", "bytes_noreuse",
+           "oi_hbm_min", "oi_hbm_noreuse", "roof_gflops_hbm", "roof_gflops_mfma")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2504_06443_amd import binding
+    return binding
+
+
+def to_dev(A):
+    import torch
+    return (torch.from_numpy(A.rowptr).cuda(), torch.from_numpy(A.colind).cuda(),
+            torch.from_numpy(A.vals).cuda())
+
+
+def make_plan(gpu, A):
+    rp, ci, v = to_dev(A)
+    return gpu.spmm_plan(A.M, A.K, rp, ci, v)
+
+
+def assert_format_equal(got, ref):
+    for k in FMT_KEYS:
+        assert got[k].dtype == ref[k].dtype and got[k].shape == ref[k].shape, k
+        assert np.array_equal(got[k].view(np.uint8), ref[k].view(np.uint8)), k
+
+
+def check_c(Cg, Cref, S):
+    Cg = Cg.astype(np.float64)
+    zero = S == 0
+    assert not Cg[zero].any(), "entries with no contributing product must be exactly 0"
+    err = np.abs(Cg - Cref)
+    worst = (err[~zero] / S[~zero]).max() if (~zero).any() else 0.0
+    assert worst <= TOL, f"max |C-Cref| / sum|ab| = {worst:.3e}"
+    return worst
+
+
+def run_product(gpu, plan, A, B, route=None, split=None):
+    import torch
+    if route is not None:
+        gpu.spmm_plan_set_route(plan, route)
+    if split is not None:
+        gpu.spmm_plan_set_split(plan, split)
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.full((A.M, B.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
+    gpu.spmm_exec(plan, Bd, Cd)
+    torch.cuda.synchronize()
+    return Cd.cpu().numpy()
+
+
+SMALL = {
+    "uniform_ragged": lambda: W.uniform_random(203, 157, 0.05, 1, empty_row_frac=0.2),
+    "dense_small": lambda: W.uniform_random(48, 40, 0.6, 2),
+    "one_row": lambda: W.uniform_random(1, 300, 0.3, 3),
+    "tall_skinny": lambda: W.uniform_random(1000, 5, 0.3, 4),
+    "banded": lambda: W.tiny_banded(M=1500, seed=5),
+    "blocks": lambda: W.clustered_blocks(2000, 5, 60, seed=6),
+    "powerlaw": lambda: W.power_law(M=3000, target_nnz=None, cap=500, seed=7),
+    "sweep_high": lambda: W.brick_sweep(0.8, M=1024, target_nnz=30000, seed=8),
+    "sweep_low": lambda: W.brick_sweep(0.05, M=1024, target_nnz=30000, seed=9),
+    "empty": lambda: W.csr_from_coo(50, 20, [], []),
+    "single": lambda: W.csr_from_coo(40, 33, [37], [32], np.array([2.5], np.float32)),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_format_and_counts_bit_exact(gpu, name):
+    A = SMALL[name]()
+    print(f"case {name}: M={A.M} K={A.K} nnz={A.nnz}", flush=True)
+    plan = make_plan(gpu, A)
+    ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+    assert_format_equal(gpu.spmm_plan_export(plan), ref)
+    for N in (1, 128):
+        got = gpu.spmm_synergy(plan, N)
+        exp = oracle.synergy(A.M, A.K, N, A.rowptr, A.colind, ref)
+        for k in INT_KEYS:
+            assert got[k] == exp[k], (k, got[k], exp[k])
+        for k in FP_KEYS:
+            assert got[k] == pytest.approx(exp[k], rel=1e-12, abs=0), k
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("N", [1, 7, 16, 33, 64, 100, 128, 130, 260])
+def test_product_all_routes(gpu, name, N):
+    A = SMALL[name]()
+    B = W.dense_b(A.K, N, 77)
+    Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+    plan = make_plan(gpu, A)
+    for route in (gpu.ROUTE_AUTO, gpu.ROUTE_MFMA, gpu.ROUTE_VALU):
+        print(f"case {name} N={N} route={route}", flush=True)
+        Cg = run_product(gpu, plan, A, B, route=route)
+        assert not np.isnan(Cg).any(), "every element of C must be written"
+        check_c(Cg, Cref, S)
+
+
+@pytest.mark.parametrize("N", [16, 32, 64, 128, 200])
+def test_integer_values_are_exact(gpu, N):
+    """Small-integer A and B: every partial sum is exact in fp32, so the result
+    must equal the fp64 oracle bit for bit -- isolates indexing from rounding."""
+    A = W.uniform_random(333, 211, 0.08, 21, integer_values=True)
+    B = np.random.default_rng(5).integers(-8, 9, size=(A.K, N)).astype(np.float32)
+    Cref = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B, want_abs=False)
+    plan = make_plan(gpu, A)
+    for route in (gpu.ROUTE_MFMA, gpu.ROUTE_VALU):
+        for split in (1, 2, 3):
+            Cg = run_product(gpu, plan, A, B, route=route, split=split)
+            assert np.array_equal(Cg.astype(np.float64), Cref), (route, split)
+
+
+def test_identity_and_permutation(gpu):
+    n, N = 1000, 64
+    B = W.dense_b(n, N, 3)
+    eye = W.csr_from_coo(n, n, np.arange(n), np.arange(n), np.ones(n, np.float32))
+    perm = np.random.default_rng(1).permutation(n)
+    pm = W.csr_from_coo(n, n, np.arange(n), perm, np.ones(n, np.float32))
+    for route in (gpu.ROUTE_MFMA, gpu.ROUTE_VALU):
+        assert np.array_equal(run_product(gpu, make_plan(gpu, eye), eye, B, route=route), B)
+        assert np.array_equal(run_product(gpu, make_plan(gpu, pm), pm, B, route=route), B[perm])
+
+
+@pytest.mark.parametrize("split", [0, 2, 3, 5])
+@pytest.mark.parametrize("N", [32, 128, 150])
+def test_split_panels_merge(gpu, split, N):
+    """Heavy panels split along K (Section 5): parts tile the panel, the merged
+    result matches the oracle and is reproducible run to run."""
+    A = W.power_law(M=2000, target_nnz=None, cap=1500, alpha=1.5, seed=31)
+    B = W.dense_b(A.K, N, 32)
+    Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+    plan = make_plan(gpu, A)
+    C1 = run_product(gpu, plan, A, B, route=gpu.ROUTE_MFMA, split=split)
+    check_c(C1, Cref, S)
+    wl = gpu.spmm_plan_worklist(plan, N)
+    fmt = gpu.spmm_plan_export(plan)
+    if split > 1:
+        assert wl["n_split_panels"] > 0
+    seen = {}
+    for panel, b0, b1, part, nparts in wl["items"]:
+        seen.setdefault(panel, []).append((part, b0, b1, nparts))
+    for panel, lst in seen.items():
+        lst.sort()
+        assert [x[0] for x in lst] == list(range(lst[0][3]))
+        assert lst[0][1] == fmt["panel_ptr"][panel] and lst[-1][2] == fmt["panel_ptr"][panel + 1]
+        for (_, _, e, _), (_, s, _, _) in zip(lst, lst[1:]):
+            assert e == s
+    C2 = run_product(gpu, plan, A, B)
+    assert np.array_equal(C1, C2)
+
+
+def test_auto_split_matches_oracle_partition(gpu):
+    """The library's Eq. 6-7 split equals the oracle's for the wave count it reports."""
+    A = W.power_law(M=4000, target_nnz=None, cap=2000, alpha=1.6, seed=41)
+    plan = make_plan(gpu, A)
+    gpu.spmm_plan_set_route(plan, gpu.ROUTE_MFMA)
+    wl = gpu.spmm_plan_worklist(plan, 128)
+    fmt = gpu.spmm_plan_export(plan)
+    nb_p = np.diff(fmt["panel_ptr"].astype(np.int64))
+    panels = [p for p in range(len(nb_p)) if nb_p[p] > 0]
+    # capacity 1 x 1 and `num_waves` work items reproduce the library's wave count
+    parts, waves = oracle.partition_counts([int(nb_p[p]) for p in panels], wl["num_waves"], 1, 1)
+    assert waves == wl["num_waves"]
+    got = {}
+    for panel, b0, b1, part, nparts in wl["items"]:
+        got.setdefault(panel, []).append((int(b0), int(b1)))
+    for p, want in zip(panels, parts):
+        base = int(fmt["panel_ptr"][p])
+        expect = [(base + lo, base + hi) for lo, hi in oracle.partition_ranges(int(nb_p[p]), want)]
+        assert sorted(got[p]) == expect, p
+
+
+def test_invalid_csr_is_rejected(gpu):
+    import torch
+    good = W.uniform_random(40, 30, 0.2, 1)
+    cases = {}
+    rp = good.rowptr.copy(); rp[5], rp[6] = rp[6], rp[5] + 0
+    if rp[5] > rp[6]:
+        cases["rowptr_not_monotone"] = (rp, good.colind, good.vals)
+    rp2 = good.rowptr.copy(); rp2[0] = 1
+    cases["rowptr_start"] = (rp2, good.colind, good.vals)
+    ci = good.colind.copy(); ci[3] = 30
+    cases["col_out_of_range"] = (good.rowptr, ci, good.vals)
+    ci2 = good.colind.copy(); ci2[0] = -1
+    cases["col_negative"] = (good.rowptr, ci2, good.vals)
+    row = int(np.argmax(np.diff(good.rowptr) >= 2))
+    s = good.rowptr[row]
+    ci3 = good.colind.copy(); ci3[s], ci3[s + 1] = ci3[s + 1], ci3[s]
+    cases["unsorted_row"] = (good.rowptr, ci3, good.vals)
+    ci4 = good.colind.copy(); ci4[s + 1] = ci4[s]
+    cases["duplicate"] = (good.rowptr, ci4, good.vals)
+    for name, (rp_, ci_, v_) in cases.items():
+        print("invalid case", name, flush=True)
+        with pytest.raises(gpu.SpmmError) as e:
+            gpu.spmm_plan(40, 30, torch.from_numpy(rp_).cuda(), torch.from_numpy(ci_).cuda(),
+                          torch.from_numpy(v_).cuda())
+        assert e.value.code == gpu.SPMM_EFORMAT, name
+    # and a valid plan still works afterwards
+    plan = make_plan(gpu, good)
+    assert gpu.spmm_plan_sizes(plan)["nnz"] == good.nnz
+
+
+def test_degenerate_sizes(gpu):
+    import torch
+    # M = 0
+    A = W.csr_from_coo(0, 10, [], [])
+    plan = make_plan(gpu, A)
+    Cd = gpu.spmm_exec(plan, torch.zeros((10, 8), device="cuda"))
+    assert tuple(Cd.shape) == (0, 8)
+    # N = 0
+    A = W.uniform_random(20, 10, 0.3, 1)
+    plan = make_plan(gpu, A)
+    Cd = gpu.spmm_exec(plan, torch.zeros((10, 0), device="cuda"))
+    assert tuple(Cd.shape) == (20, 0)
+    # explicit zeros are kept and give exact zeros
+    A = W.csr_from_coo(20, 9, [1, 1, 18], [2, 5, 5], np.array([0.0, -0.0, 1.0], np.float32))
+    plan = make_plan(gpu, A)
+    ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+    assert_format_equal(gpu.spmm_plan_export(plan), ref)
+    B = W.dense_b(9, 16, 1)
+    Cg = run_product(gpu, plan, A, B, route=gpu.ROUTE_MFMA)
+    assert not Cg[1].any() and np.array_equal(Cg[18], B[5])
+
+
+def test_config1_tiny_banded_full(gpu):
+    A, Ns = W.config(1)
+    plan = make_plan(gpu, A)
+    ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+    assert_format_equal(gpu.spmm_plan_export(plan), ref)
+    for N in Ns + [128]:
+        B = W.dense_b(A.K, N, 1001)
+        Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+        for route in (gpu.ROUTE_AUTO, gpu.ROUTE_MFMA, gpu.ROUTE_VALU):
+            check_c(run_product(gpu, plan, A, B, route=route), Cref, S)
