@@ -141,7 +141,7 @@ int spmm_plan_export(const spmm_plan_t *plan, uint32_t *panel_ptr /* host [P+1] 
  *
  * spmm_plan_set_route: which kernel handles which panel (enum spmm_route).
  * spmm_plan_set_split: how heavy panels are split along K into virtual panels:
- *   parts = 0  Eq. 6-7: parts_p = ceil( blocks_p / avg_blocks / num_waves ),
+ *   parts = 0  Eq. 6-7: parts_p = round( blocks_p / avg_blocks / num_waves ), at least 1,
  *              num_waves = ceil(work items / (CUs * resident waves per CU))
  *   parts = 1  never split
  *   parts > 1  split every panel that has at least `parts` blocks into `parts`

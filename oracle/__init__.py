@@ -166,7 +166,8 @@ def partition_counts(nbricks_per_panel, total_work_items: int, num_cus: int,
     num_waves = ceil(total_work_items / (num_cus * resident_per_cu)), at least 1;
     num_loads_p = blocks_p / average blocks over all panels (Eq. 6);
     partition_ratio_p = num_loads_p / num_waves (Eq. 7);
-    parts_p = max(1, ceil(partition_ratio_p)), evaluated in integers.
+    parts_p = max(1, round-half-up(partition_ratio_p)), evaluated in integers
+    (the paper gives no rounding rule: a ratio of exactly 1 must not split).
     Returns (parts list, num_waves)."""
     blocks = [_ceil_div(int(b), 4) for b in nbricks_per_panel]
     P = len(blocks)
@@ -177,7 +178,7 @@ def partition_counts(nbricks_per_panel, total_work_items: int, num_cus: int,
         if total == 0 or b == 0:
             parts.append(1)
         else:
-            parts.append(max(1, _ceil_div(b * P, total * waves)))
+            parts.append(max(1, (2 * b * P + total * waves) // (2 * total * waves)))
     return parts, waves
 
 

@@ -112,7 +112,8 @@ int classify(int64_t nnz, int64_t nb) {
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Eq. 6-7 in integers: parts_p = max(1, ceil(blocks_p * P / (total_blocks * waves))).
+// Eq. 6-7 in integers: partition_ratio_p = blocks_p * P / (total_blocks * waves), rounded to
+// the nearest integer (halves up), at least 1.
 void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, int64_t capacity,
                       uint32_t* parts, int64_t* waves_out) {
   int64_t total = 0;
@@ -125,7 +126,7 @@ void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, in
       // blocks * P can exceed 2^63 only for absurd sizes; use 128-bit to be safe
       const __int128 num = (__int128)blocks * P;
       const __int128 den = (__int128)total * waves;
-      q = (int64_t)((num + den - 1) / den);
+      q = (int64_t)((2 * num + den) / (2 * den));
     }
     parts[p] = (uint32_t)std::max<int64_t>(1, q);
   }
@@ -330,17 +331,21 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   }
 
   // ---- a2/a3: brick columns and patterns
-  HIP_TRY(dev_alloc(&pl->brick_cols, pl->nb * kBrickK));
-  HIP_TRY(dev_alloc(&pl->brick_mask, pl->nb));
-  HIP_TRY(dev_alloc(&pl->brick_valptr, pl->nb + 1));
-  HIP_TRY(dev_alloc(&pl->vals, nnz + 1));
+  // spare entries past the end of each array (see BrickFormat)
+  HIP_TRY(dev_alloc(&pl->brick_cols, (pl->nb + kFormatPad) * kBrickK));
+  HIP_TRY(dev_alloc(&pl->brick_mask, pl->nb + kFormatPad));
+  HIP_TRY(dev_alloc(&pl->brick_valptr, pl->nb + 1 + kFormatPad));
+  HIP_TRY(dev_alloc(&pl->vals, nnz + 64));
+  HIP_TRY(hipMemsetAsync(pl->brick_cols + pl->nb * kBrickK, 0, kFormatPad * kBrickK * 4, s));
+  HIP_TRY(hipMemsetAsync(pl->brick_mask + pl->nb, 0, kFormatPad * 8, s));
+  HIP_TRY(launch_fill_u32(pl->brick_valptr + pl->nb + 1, kFormatPad, (uint32_t)nnz, s));
+  HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, 64 * sizeof(float), s));
   HIP_TRY(dev_alloc(&ent_brick, nnz));
   HIP_TRY(dev_alloc(&ent_bit, nnz));
   HIP_TRY(dev_alloc(&col_seen, K));
   HIP_TRY(launch_fill_u32(pl->brick_cols, pl->nb * kBrickK, kPadCol, s));
   HIP_TRY(launch_fill_u64(pl->brick_mask, pl->nb, 0ull, s));
   HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
-  HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, sizeof(float), s));
   HIP_TRY(launch_rank_scatter(rowptr, colind, ent_row, first, first_scan, pl->panel_ptr, M, nnz,
                               pl->brick_cols, pl->brick_mask, ent_brick, ent_bit, col_seen, s));
 
@@ -420,7 +425,8 @@ int spmm_exec(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream
   int status = build_worklist(pl, N, s, &wl);
   if (status != SPMM_OK) return status;
   const BrickFormat f{pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals};
-  HIP_TRY(launch_spmm_mfma(f, wl->d_items, wl->info.n_mfma_items, B, C, wl->d_partial, pl->M, N, s));
+  HIP_TRY(launch_spmm_mfma(f, wl->d_items, wl->info.n_mfma_items, B, C, wl->d_partial, pl->M, N,
+                           pl->K, s));
   HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, wl->d_valu_panels,
                            wl->info.n_valu_panels, B, C, pl->M, N, s));
   HIP_TRY(launch_merge(wl->d_merge, wl->n_merge, wl->d_partial, C, pl->M, N, s));

@@ -18,8 +18,10 @@
 // LDS staging is needed because a B row of a panel is used by exactly one
 // brick when panels are 16 rows high.
 //
-// Loads are software-pipelined: while the MFMAs of brick b issue, the values
-// and B rows of brick b+1 and the metadata of brick b+2 are in flight.
+// Loads are software-pipelined through a ring of register stages: while the
+// MFMAs of brick b issue, the values and B rows of the next kStages bricks are
+// in flight; brick metadata is fetched 16 bricks at a time with coalesced loads
+// and distributed by cross-lane reads.
 //
 // Vector-ALU CSR kernel (the paper's "scalar core" path): one wavefront per
 // row, one coalesced B-row load and one FMA per stored entry.  Used for panels
@@ -34,6 +36,10 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kWavesPerBlock = 4;
+constexpr int kXcds = 8;     // accelerator complex dies of an MI355X, each with its own L2
+constexpr int kStages = 4;   // bricks whose loads are in flight per wavefront (MFMA kernel)
+constexpr int kChunk = 16;   // bricks per coalesced metadata fetch
+static_assert(kChunk % kStages == 0 && kChunk == 16, "stage and lane mapping assume this");
 
 template <int V> struct Vec;
 template <> struct Vec<1> { typedef float type; };
@@ -96,7 +102,13 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma(
   constexpr int V = T < 4 ? T : 4;
   constexpr int NV = T / V;
   const int lane = threadIdx.x & 63;
-  const int64_t item_id = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own
+  // L2.  Give each XCD a contiguous range of work items, so that neighbouring
+  // panels -- which share most of their B rows in banded matrices -- meet in one
+  // L2 instead of every XCD fetching every B row.
+  const uint32_t per_xcd = gridDim.x / kXcds;  // the launcher pads gridDim.x to a multiple
+  const uint32_t vblock = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  const int64_t item_id = (int64_t)vblock * kWavesPerBlock + (threadIdx.x >> 6);
   if (item_id >= n_items) return;  // whole wavefront leaves together
   const WorkItem it = items[item_id];
   const uint32_t panel = __builtin_amdgcn_readfirstlane(it.panel);
@@ -116,46 +128,73 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma(
 
   if (b_begin < b_end) {
     const uint32_t last = b_end - 1;
-    struct Meta { uint64_t mask; uint32_t off; uint32_t col; };
-    struct Stage { uint64_t mask; float a_raw; float bv[T]; };
-    auto load_meta = [&](uint32_t b) {
-      return Meta{f.brick_mask[b], f.brick_valptr[b], f.brick_cols[(int64_t)b * kBrickK + kq]};
+    const uint32_t nbricks = b_end - b_begin;
+    constexpr int R = kStages;   // bricks in flight per wavefront
+    constexpr int CH = kChunk;   // bricks per metadata chunk
+
+    // Metadata of CH consecutive bricks, fetched with three coalesced loads and
+    // handed out per brick by cross-lane reads (no memory latency per brick):
+    //   cols: lane l holds brick_cols[4*(base + l/4) + l%4]
+    //   mask, off: lane l holds brick_mask / brick_valptr of brick base + l%16
+    struct Chunk { uint32_t cols; uint32_t mask_lo, mask_hi; uint32_t off; };
+    auto load_chunk = [&](uint32_t base) {
+      const uint32_t bc = min(base + (uint32_t)(lane >> 2), last);
+      const uint32_t bm = min(base + (uint32_t)(lane & (CH - 1)), last);
+      const uint64_t m = f.brick_mask[bm];
+      return Chunk{f.brick_cols[(int64_t)bc * kBrickK + (lane & 3)], (uint32_t)m,
+                   (uint32_t)(m >> 32), f.brick_valptr[bm]};
     };
-    // Issue the loads of one brick.  The value index is the number of pattern
-    // bits below this lane's bit; lanes whose bit is clear read a neighbouring
-    // value (vals has one pad element) that compute() discards.
-    auto issue = [&](const Meta& m, Stage& st) {
-      st.mask = m.mask;
-      st.a_raw = f.vals[(int64_t)m.off + __popcll(m.mask & below)];
-      load_b<T, ALIGNED>(B + (int64_t)(m.col == kPadCol ? 0u : m.col) * N, N, ncol0, st.bv);
+
+    // R register stages; stage s holds the loads of one brick in flight.
+    uint64_t st_mask[R];
+    float st_a[R];
+    float st_b[R][T];
+
+    // Issue the loads of brick i of the chunk into stage s.  The value index is
+    // the number of pattern bits below this lane's bit; lanes whose bit is clear
+    // read a neighbouring value (vals has one pad element) that is discarded.
+    auto issue = [&](const Chunk& ch, uint32_t i, int s) {
+      const uint32_t mlo = __builtin_amdgcn_readlane(ch.mask_lo, i);
+      const uint32_t mhi = __builtin_amdgcn_readlane(ch.mask_hi, i);
+      const uint32_t off = __builtin_amdgcn_readlane(ch.off, i);
+      const uint64_t mask = ((uint64_t)mhi << 32) | mlo;
+      const uint32_t col = __builtin_amdgcn_ds_bpermute(4 * (4 * i + kq), ch.cols);
+      st_mask[s] = mask;
+      st_a[s] = f.vals[(int64_t)off + __popcll(mask & below)];
+      load_b<T, ALIGNED>(B + (int64_t)(col == kPadCol ? 0u : col) * N, N, ncol0, st_b[s]);
     };
-    auto compute = [&](const Stage& st) {
-      const float a = ((st.mask >> bit) & 1ull) ? st.a_raw : 0.f;
+    auto compute = [&](int s) {
+      const float a = ((st_mask[s] >> bit) & 1ull) ? st_a[s] : 0.f;
 #pragma unroll
       for (int u = 0; u < T; ++u)
-        acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, st.bv[u], acc[u], 0, 0, 0);
+        acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, st_b[s][u], acc[u], 0, 0, 0);
     };
-    // While brick b computes, the loads of brick b+1 and the metadata of brick
-    // b+2 are in flight (indices clamped to the last brick: harmless re-reads).
-    // The prologue values pass through empty asm statements so that they are
-    // not plain loads: otherwise the compiler merges each prologue load with its
-    // in-loop twin into one load at the top of the loop, which undoes the
-    // prefetch distance.
-    Stage cur;
-    issue(load_meta(b_begin), cur);
-    asm volatile("" : "+v"(cur.a_raw));
-    Meta m1 = load_meta(min(b_begin + 1, last));
-    asm volatile("" : "+v"(m1.col));
-    m1.off = __builtin_amdgcn_readfirstlane(m1.off);
-    m1.mask = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(m1.mask >> 32)) << 32) |
-              (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)m1.mask);
-    for (uint32_t b = b_begin; b < b_end; ++b) {
-      const Meta m2 = load_meta(min(b + 2, last));
-      Stage nxt;
-      issue(m1, nxt);
-      compute(cur);
+
+    // The first chunk passes through an empty asm statement so that it is not a
+    // plain load: otherwise the compiler merges it with the in-loop chunk load
+    // into one load at the top of the loop, serialising that latency.
+    Chunk cur = load_chunk(b_begin);
+    asm volatile("" : "+v"(cur.cols), "+v"(cur.mask_lo), "+v"(cur.mask_hi), "+v"(cur.off));
+
+    // Step g computes brick g-R from stage g%R and then refills that stage with
+    // brick g, so R bricks' loads are in flight while the MFMAs issue.  Refills
+    // are unconditional (past the end they re-read the last brick, which is
+    // harmless and keeps the compiler's count of outstanding loads exact); only
+    // the MFMAs are skipped for steps that hold no brick.
+    const uint32_t total = nbricks + R;
+    for (uint32_t c = 0; c < total; c += CH) {
+      const Chunk nxt = load_chunk(b_begin + c + CH);
+#pragma unroll 1
+      for (uint32_t i0 = 0; i0 < (uint32_t)CH; i0 += R) {
+        if (c + i0 >= total) break;
+#pragma unroll
+        for (int s = 0; s < R; ++s) {
+          const uint32_t g = c + i0 + s;
+          if (g >= (uint32_t)R && g - R < nbricks) compute(s);
+          issue(cur, i0 + s, s);
+        }
+      }
       cur = nxt;
-      m1 = m2;
     }
   }
 
@@ -185,6 +224,170 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma(
 #pragma unroll
           for (int w = 0; w < V; ++w)
             if (n + w < N) out[v * N + n + w] = tmp[w];
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ MFMA, fast path
+// Same lane mapping as above for the common case: N a multiple of the vector
+// width, 16-byte aligned B and C, and B smaller than 4 GiB (32-bit byte offsets).
+//
+// Vector-ALU instructions overlap only partly with MFMAs on a SIMD (measured:
+// about 2 cycles of MFMA time lost per extra VALU instruction), so the per-brick
+// VALU work is kept small:
+//   * pattern and value offset of each brick come through the scalar cache into
+//     SGPRs (8 bricks per fetch), not through vector loads and cross-lane reads;
+//   * the B-row byte offsets of 8 bricks are computed once per 8 bricks (one
+//     lane per brick column) and handed out with ds_bpermute, which issues on
+//     the LDS port;
+//   * loads use a scalar base plus a 32-bit lane offset.
+// The arrays behind BrickFormat carry kFormatPad spare bricks at the end, so
+// metadata is fetched 8 bricks at a time without clamping, and the loads issued
+// for the few steps past a work item's last brick touch valid memory; their
+// data is never used.
+constexpr int kFastChunk = 8;
+
+template <int T>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
+    const uint32_t* __restrict__ brick_cols, const uint64_t* __restrict__ brick_mask,
+    const uint32_t* __restrict__ brick_valptr, const float* __restrict__ vals,
+    const WorkItem* __restrict__ items, int64_t n_items, const float* __restrict__ B,
+    float* __restrict__ C, float* __restrict__ partial, int64_t M, int64_t N, uint32_t k_last) {
+  // (the format arrays are separate __restrict__ parameters, not a struct, so that
+  // the compiler knows they are read-only here and may use the scalar cache)
+  constexpr int V = T < 4 ? T : 4;
+  constexpr int NV = T / V;
+  constexpr int R = kStages;
+  constexpr int CH = kFastChunk;
+  static_assert(CH % R == 0 && CH * kBrickK <= 64, "stage and lane mapping assume this");
+
+  const int lane = threadIdx.x & 63;
+  // contiguous range of work items per XCD (workgroups go to XCDs round-robin)
+  const uint32_t per_xcd = gridDim.x / kXcds;
+  const uint32_t vblock = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  const int64_t item_id = (int64_t)vblock * kWavesPerBlock + (threadIdx.x >> 6);
+  if (item_id >= n_items) return;  // whole wavefront leaves together
+  const WorkItem it = items[item_id];
+  const uint32_t panel = __builtin_amdgcn_readfirstlane(it.panel);
+  const uint32_t b_begin = __builtin_amdgcn_readfirstlane(it.brick_begin);
+  const uint32_t b_end = __builtin_amdgcn_readfirstlane(it.brick_end);
+  const uint32_t slot = __builtin_amdgcn_readfirstlane(it.slot);
+
+  const int j = lane & 15;
+  const int kq = lane >> 4;
+  const int bit = 4 * j + kq;
+  const uint64_t below = (1ull << bit) - 1ull;
+  const int64_t ncol0 = (int64_t)blockIdx.y * (16 * T) + V * j;
+  const uint32_t row_bytes = (uint32_t)N * 4u;
+  // byte offset of this lane's vectors inside a B row (columns >= N: clamped, never stored)
+  uint32_t lane_off[NV];
+#pragma unroll
+  for (int q = 0; q < NV; ++q)
+    lane_off[q] = (uint32_t)min<int64_t>(ncol0 + q * 16 * V, N - V) * 4u;
+  const uint32_t perm_base = 4u * (uint32_t)kq;  // ds_bpermute byte address of lane kq
+
+  float4_t acc[T];
+#pragma unroll
+  for (int u = 0; u < T; ++u) acc[u] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+  if (b_begin < b_end) {
+    const uint32_t nbricks = b_end - b_begin;
+    const char* Bbytes = reinterpret_cast<const char*>(B);
+
+    struct Meta { uint64_t mask[CH]; uint32_t off[CH]; };
+    auto load_meta = [&](uint32_t base) {   // uniform addresses: scalar loads
+      Meta m;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) { m.mask[i] = brick_mask[base + i]; m.off[i] = brick_valptr[base + i]; }
+      return m;
+    };
+    // lane 4*i + c: byte offset of B row brick_cols[4*(base+i) + c]; pad columns
+    // (0xFFFFFFFF) clamp to the last row, which is harmless since A is 0 there
+    auto load_rowoff = [&](uint32_t base) {
+      const uint32_t c = brick_cols[(int64_t)base * kBrickK + (lane & (CH * kBrickK - 1))];
+      return min(c, k_last) * row_bytes;
+    };
+
+    uint64_t st_mask[R];
+    float st_a[R];
+    float st_b[R][T];
+    auto issue = [&](uint64_t mask, uint32_t off, uint32_t rowoff_reg, int i, int s) {
+      st_mask[s] = mask;
+      st_a[s] = vals[(int64_t)off + __popcll(mask & below)];
+      const uint32_t ro = __builtin_amdgcn_ds_bpermute(perm_base + 16u * i, rowoff_reg);
+#pragma unroll
+      for (int q = 0; q < NV; ++q) {
+        float tmp[V];
+        load_vec<V>(reinterpret_cast<const float*>(Bbytes + (ro + lane_off[q])), tmp);
+#pragma unroll
+        for (int w = 0; w < V; ++w) st_b[s][q * V + w] = tmp[w];
+      }
+    };
+    auto compute = [&](int s) {
+      const float a = ((st_mask[s] >> bit) & 1ull) ? st_a[s] : 0.f;
+#pragma unroll
+      for (int u = 0; u < T; ++u)
+        acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, st_b[s][u], acc[u], 0, 0, 0);
+    };
+
+    Meta cur = load_meta(b_begin);
+    uint32_t ro_cur = load_rowoff(b_begin);
+    // keep the first fetch from being merged with the in-loop fetch into one
+    // load at the top of the loop (which would expose its latency every chunk)
+    asm volatile("" : "+v"(ro_cur));
+#pragma unroll
+    for (int i = 0; i < CH; ++i) asm volatile("" : "+s"(cur.mask[i]), "+s"(cur.off[i]));
+
+    // Step g computes brick g-R from stage g%R and then refills that stage with
+    // brick g, so R bricks' loads are in flight while the MFMAs issue.  Refills
+    // are unconditional up to the next multiple of R past the end (keeps the
+    // compiler's count of outstanding loads exact); only MFMAs are skipped for
+    // steps that hold no brick.
+    const uint32_t total = nbricks + R;
+    for (uint32_t c = 0; c < total; c += CH) {
+      const Meta nxt = load_meta(b_begin + c + CH);
+      const uint32_t ro_nxt = load_rowoff(b_begin + c + CH);
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const uint32_t g = c + i;
+        if (i % R == 0 && i > 0 && g >= total) break;
+        if (g >= (uint32_t)R && g - R < nbricks) compute(i % R);
+        issue(cur.mask[i], cur.off[i], ro_cur, i, i % R);
+      }
+      cur = nxt;
+      ro_cur = ro_nxt;
+    }
+  }
+
+  // acc[q*V + w][v] = C[row 4*kq + v][ncol0 + q*16*V + w]
+  float* out;
+  int64_t rows_left;
+  if (slot == kNoSlot) {
+    const int64_t row0 = (int64_t)panel * kPanel + 4 * kq;
+    out = C + row0 * N;
+    rows_left = M - row0;
+  } else {
+    out = partial + ((int64_t)slot * kPanel + 4 * kq) * N;
+    rows_left = 4;
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    if (v < rows_left) {
+#pragma unroll
+      for (int q = 0; q < NV; ++q) {
+        const int64_t ncol = ncol0 + q * 16 * V;
+        if (ncol < N) {
+          typedef typename Vec<V>::type vt;
+          vt t;
+          if constexpr (V == 1) t = acc[q][v];
+          else {
+#pragma unroll
+            for (int w = 0; w < V; ++w) t[w] = acc[q * V + w][v];
+          }
+          // C is written once and not read again here: stream it past the caches
+          __builtin_nontemporal_store(t, reinterpret_cast<vt*>(out + v * N + ncol));
         }
       }
     }
@@ -275,7 +478,8 @@ template <int T, bool ALIGNED>
 hipError_t launch_mfma_t(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                          const float* B, float* C, float* partial, int64_t M, int64_t N,
                          hipStream_t s) {
-  const unsigned gx = (unsigned)((n_items + kWavesPerBlock - 1) / kWavesPerBlock);
+  unsigned gx = (unsigned)((n_items + kWavesPerBlock - 1) / kWavesPerBlock);
+  gx = (gx + kXcds - 1) / kXcds * kXcds;  // whole rounds over the XCDs
   const unsigned gy = (unsigned)((N + 16 * T - 1) / (16 * T));
   hipLaunchKernelGGL((k_spmm_mfma<T, ALIGNED>), dim3(gx, gy), dim3(64 * kWavesPerBlock), 0, s, f,
                      items, n_items, B, C, partial, M, N);
@@ -308,12 +512,29 @@ int mfma_resident_waves_per_cu(int n_tile, bool aligned) {
 
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
-                            hipStream_t s) {
+                            int64_t K, hipStream_t s) {
   if (n_items == 0 || N == 0) return hipSuccess;
   const int tile = mfma_tile_for(N);
   const int V = tile >= 64 ? 4 : tile / 16;
   const bool al = (N % V == 0) && ptr_aligned16(B) && ptr_aligned16(C) &&
                   (partial == nullptr || ptr_aligned16(partial));
+  if (al && K > 0 && (double)K * (double)N * 4.0 < 4294967296.0) {
+    unsigned gx = (unsigned)((n_items + kWavesPerBlock - 1) / kWavesPerBlock);
+    gx = (gx + kXcds - 1) / kXcds * kXcds;  // whole rounds over the XCDs
+    const dim3 grid(gx, (unsigned)((N + tile - 1) / tile)), block(64 * kWavesPerBlock);
+    const uint32_t k_last = (uint32_t)(K - 1);
+#define SPMM_LAUNCH_FAST(TT)                                                              \
+  hipLaunchKernelGGL((k_spmm_mfma_fast<TT>), grid, block, 0, s, f.brick_cols, f.brick_mask, \
+                     f.brick_valptr, f.vals, items, n_items, B, C, partial, M, N, k_last)
+    switch (tile) {
+      case 16: SPMM_LAUNCH_FAST(1); break;
+      case 32: SPMM_LAUNCH_FAST(2); break;
+      case 64: SPMM_LAUNCH_FAST(4); break;
+      default: SPMM_LAUNCH_FAST(8); break;
+    }
+#undef SPMM_LAUNCH_FAST
+    return hipGetLastError();
+  }
   switch (tile) {
     case 16: return launch_mfma_t<1, true>(f, items, n_items, B, C, partial, M, N, s);
     case 32: return al ? launch_mfma_t<2, true>(f, items, n_items, B, C, partial, M, N, s)

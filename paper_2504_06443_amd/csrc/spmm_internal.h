@@ -82,18 +82,23 @@ hipError_t launch_scan_popc64(const uint64_t* in, int64_t n, uint32_t* out, uint
                               hipStream_t s);
 
 // ---- exec (a6..a8) -------------------------------------------------------
+// Device arrays of the brick format.  Each carries spare entries past its end
+// (kFormatPad bricks' worth: zero columns and patterns, value offsets equal to
+// nnz, zero values) so that kernels may fetch metadata a few bricks past a work
+// item's last brick without clamping.
+constexpr int kFormatPad = 32;
 struct BrickFormat {
-  const uint32_t* brick_cols;
-  const uint64_t* brick_mask;
-  const uint32_t* brick_valptr;
-  const float* vals;   // nnz + 1 floats (one pad element)
+  const uint32_t* brick_cols;    // 4 * (nb + kFormatPad)
+  const uint64_t* brick_mask;    // nb + kFormatPad
+  const uint32_t* brick_valptr;  // nb + 1 + kFormatPad
+  const float* vals;             // nnz + 64
 };
 
 int mfma_tile_for(int64_t N);   // columns of C per wavefront: 16, 32, 64 or 128
 int mfma_resident_waves_per_cu(int n_tile, bool aligned);
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
-                            hipStream_t s);
+                            int64_t K, hipStream_t s);
 hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const float* vals,
                             const uint32_t* panels, int64_t n_panels, const float* B, float* C,
                             int64_t M, int64_t N, hipStream_t s);

@@ -1,0 +1,83 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration
+bench.py times (automatic routing and splitting).  The format and the synergy
+counts are compared bit for bit with the CPU oracle; C is compared on sampled
+rows the oracle computes one by one, and on a whole-matrix property
+(C x = A (B x) for a random x, evaluated by the oracle in fp64)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_06443_amd import workloads as W
+from test_gpu_parity import (FMT_KEYS, INT_KEYS, TOL, assert_format_equal, make_plan)
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2504_06443_amd import binding
+    return binding
+
+
+def check_full(gpu, A, N, tag, check_format=True, routes=("auto",)):
+    import torch
+    print(f"{tag}: M={A.M} nnz={A.nnz} N={N}", flush=True)
+    plan = make_plan(gpu, A)
+    if check_format:
+        ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+        assert_format_equal(gpu.spmm_plan_export(plan), ref)
+        got, exp = gpu.spmm_synergy(plan, N), oracle.synergy(A.M, A.K, N, A.rowptr, A.colind, ref)
+        for k in INT_KEYS:
+            assert got[k] == exp[k], k
+        print(f"{tag}: format and counts bit-exact, alpha={got['alpha_brick']:.3f}", flush=True)
+    B = W.dense_b(A.K, N, 4242)
+    Bd = torch.from_numpy(B).cuda()
+    rng = np.random.default_rng(99)
+    rows = np.unique(np.concatenate([rng.integers(0, A.M, 3000), np.arange(0, 48),
+                                     np.arange(A.M - 48, A.M),
+                                     np.argsort(np.diff(A.rowptr))[-32:]]))   # heaviest rows too
+    Cref, S = oracle.spmm_rows_f64(rows, A.rowptr, A.colind, A.vals, B)
+    x = rng.standard_normal(N)
+    y_ref, y_abs = oracle.spmm_f64(A.rowptr, A.colind, A.vals,
+                                   (B.astype(np.float64) @ x).astype(np.float32)[:, None])
+    for route in routes:
+        gpu.spmm_plan_set_route(plan, {"auto": 0, "mfma": 1, "valu": 2}[route])
+        Cd = torch.full((A.M, N), float("nan"), dtype=torch.float32, device="cuda")
+        gpu.spmm_exec(plan, Bd, Cd)
+        torch.cuda.synchronize()
+        assert not torch.isnan(Cd).any().item(), "every element of C must be written"
+        Cg = Cd[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+        zero = S == 0
+        assert not Cg[zero].any()
+        worst = (np.abs(Cg - Cref)[~zero] / S[~zero]).max()
+        assert worst <= TOL, f"{tag} {route}: sampled rows error {worst:.3e}"
+        # whole-matrix property; B x was rounded to fp32 for the oracle, so allow that much
+        y = (Cd.double() @ torch.from_numpy(x).cuda()).cpu().numpy()
+        scale = Cd.abs().double().matmul(torch.from_numpy(np.abs(x)).cuda()).cpu().numpy() + 1e-30
+        assert (np.abs(y - y_ref[:, 0]) / scale).max() < 1e-4, f"{tag} {route}: C x != A (B x)"
+        print(f"{tag} {route}: max sampled error {worst:.2e}", flush=True)
+
+
+def test_config2_clustered(gpu):
+    A, Ns = W.config(2)
+    check_full(gpu, A, Ns[0], "config2", routes=("auto", "valu"))
+
+
+def test_config3_powerlaw(gpu):
+    A, Ns = W.config(3)
+    check_full(gpu, A, Ns[0], "config3", routes=("auto", "mfma"))
+
+
+@pytest.mark.parametrize("fill", [0.05, 0.2, 0.8])
+def test_config5_sweep(gpu, fill):
+    A, Ns = W.config(5, fill=fill)
+    for N in (16, 128, 512):
+        check_full(gpu, A, N, f"config5 f={fill}", check_format=(N == 16), routes=("mfma", "valu"))
+
+
+def test_config4_fem(gpu):
+    A, Ns = W.config(4)
+    for N in Ns:
+        check_full(gpu, A, N, "config4", check_format=(N == Ns[0]))
