@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="clustered_262k")
     ap.add_argument("--n", type=int, default=0, help="columns of B (default: the workload's)")
-    ap.add_argument("--route", default="auto", choices=["auto", "mfma", "valu"])
+    ap.add_argument("--route", default="auto", choices=["auto", "mfma", "valu", "class"])
     ap.add_argument("--split", type=int, default=0)
     ap.add_argument("--cold", action="store_true",
                     help="rotate over several B/C pairs so that no step finds its operands in cache")
@@ -134,7 +134,7 @@ def main():
     plan_ms = (time.perf_counter() - t0) * 1e3
     spmm.spmm_plan_destroy(plan2)
 
-    spmm.spmm_plan_set_route(plan, {"auto": 0, "mfma": 1, "valu": 2}[args.route])
+    spmm.spmm_plan_set_route(plan, {"auto": 0, "mfma": 1, "valu": 2, "class": 3}[args.route])
     spmm.spmm_plan_set_split(plan, args.split)
     syn = spmm.spmm_synergy(plan, N)
     wl = spmm.spmm_plan_worklist(plan, N)

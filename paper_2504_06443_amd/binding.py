@@ -25,7 +25,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 SPMM_OK, SPMM_EINVAL, SPMM_EFORMAT, SPMM_ENOMEM, SPMM_EHIP, SPMM_ELIMIT = 0, -1, -2, -3, -4, -5
-ROUTE_AUTO, ROUTE_MFMA, ROUTE_VALU = 0, 1, 2
+ROUTE_AUTO, ROUTE_MFMA, ROUTE_VALU, ROUTE_CLASS = 0, 1, 2, 3
 CLASS_NAMES = ("Low", "Medium", "High")
 
 EXPORTED = (

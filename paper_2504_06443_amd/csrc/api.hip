@@ -77,6 +77,7 @@ struct spmm_plan {
   float* csr_vals = nullptr;
   // host copies used by the work-list builder and the synergy model
   std::vector<uint32_t> h_panel_ptr;
+  std::vector<uint32_t> h_panel_nnzptr;   // first CSR entry of each panel
   std::vector<uint8_t> h_panel_class;
   unsigned long long h_counters[kNumCounters] = {};
   int64_t n_active_cols = 0;
@@ -158,7 +159,8 @@ int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** ou
     if (cls == 255) to_mfma = false;  // empty panel: the CSR kernel stores its zero rows
     else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
     else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
-    else to_mfma = cls != SPMM_LOW;
+    else if (pl->route == SPMM_ROUTE_CLASS) to_mfma = cls != SPMM_LOW;
+    else to_mfma = true;  // AUTO: the brick kernel is the faster one for every class on MI355X
     if (to_mfma) {
       mfma_panels.push_back((uint32_t)p);
       nbricks.push_back(pl->h_panel_ptr[p + 1] - pl->h_panel_ptr[p]);
@@ -384,12 +386,15 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   // ---- host copies for the work-list builder and the model
   try {
     pl->h_panel_ptr.resize((size_t)P + 1);
+    pl->h_panel_nnzptr.resize((size_t)P + 1);
     pl->h_panel_class.resize((size_t)std::max<int64_t>(P, 1));
   } catch (const std::bad_alloc&) {
     status = fail(SPMM_ENOMEM, "host allocation failed");
     goto done;
   }
   HIP_TRY(hipMemcpyAsync(pl->h_panel_ptr.data(), pl->panel_ptr, (size_t)(P + 1) * sizeof(uint32_t),
+                         hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(pl->h_panel_nnzptr.data(), panel_nnzptr, (size_t)(P + 1) * sizeof(uint32_t),
                          hipMemcpyDeviceToHost, s));
   if (P > 0)
     HIP_TRY(hipMemcpyAsync(pl->h_panel_class.data(), panel_class, (size_t)P,
@@ -495,7 +500,7 @@ done:
 
 int spmm_plan_set_route(spmm_plan_t* pl, int route) {
   if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
-  if (route < SPMM_ROUTE_AUTO || route > SPMM_ROUTE_VALU) return fail(SPMM_EINVAL, "bad route");
+  if (route < SPMM_ROUTE_AUTO || route > SPMM_ROUTE_CLASS) return fail(SPMM_EINVAL, "bad route");
   if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
   pl->route = route;
   pl->drop_lists();

@@ -298,9 +298,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
 
     struct Meta { uint64_t mask[CH]; uint32_t off[CH]; };
     auto load_meta = [&](uint32_t base) {   // uniform addresses: scalar loads
+      // one pointer per array, constant offsets: lets the loads merge into wide scalar loads
+      const uint64_t* __restrict__ mp = brick_mask + base;
+      const uint32_t* __restrict__ op = brick_valptr + base;
       Meta m;
 #pragma unroll
-      for (int i = 0; i < CH; ++i) { m.mask[i] = brick_mask[base + i]; m.off[i] = brick_valptr[base + i]; }
+      for (int i = 0; i < CH; ++i) { m.mask[i] = mp[i]; m.off[i] = op[i]; }
       return m;
     };
     // lane 4*i + c: byte offset of B row brick_cols[4*(base+i) + c]; pad columns
@@ -313,10 +316,9 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     uint64_t st_mask[R];
     float st_a[R];
     float st_b[R][T];
-    auto issue = [&](uint64_t mask, uint32_t off, uint32_t rowoff_reg, int i, int s) {
+    auto issue = [&](uint64_t mask, uint32_t off, uint32_t ro, int s) {
       st_mask[s] = mask;
       st_a[s] = vals[(int64_t)off + __popcll(mask & below)];
-      const uint32_t ro = __builtin_amdgcn_ds_bpermute(perm_base + 16u * i, rowoff_reg);
 #pragma unroll
       for (int q = 0; q < NV; ++q) {
         float tmp[V];
@@ -346,6 +348,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     // compiler's count of outstanding loads exact); only MFMAs are skipped for
     // steps that hold no brick.
     const uint32_t total = nbricks + R;
+    uint32_t ro_next = __builtin_amdgcn_ds_bpermute(perm_base, ro_cur);
     for (uint32_t c = 0; c < total; c += CH) {
       const Meta nxt = load_meta(b_begin + c + CH);
       const uint32_t ro_nxt = load_rowoff(b_begin + c + CH);
@@ -354,7 +357,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
         const uint32_t g = c + i;
         if (i % R == 0 && i > 0 && g >= total) break;
         if (g >= (uint32_t)R && g - R < nbricks) compute(i % R);
-        issue(cur.mask[i], cur.off[i], ro_cur, i, i % R);
+        // this lane's row offset was fetched across lanes one step ago (its LDS-port latency
+        // hides behind the MFMAs above); fetch the next brick's now
+        const uint32_t ro = ro_next;
+        ro_next = (i + 1 < CH) ? __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_cur)
+                               : __builtin_amdgcn_ds_bpermute(perm_base, ro_nxt);
+        issue(cur.mask[i], cur.off[i], ro, i % R);
       }
       cur = nxt;
       ro_cur = ro_nxt;

@@ -43,7 +43,7 @@ def check_full(gpu, A, N, tag, check_format=True, routes=("auto",)):
     y_ref, y_abs = oracle.spmm_f64(A.rowptr, A.colind, A.vals,
                                    (B.astype(np.float64) @ x).astype(np.float32)[:, None])
     for route in routes:
-        gpu.spmm_plan_set_route(plan, {"auto": 0, "mfma": 1, "valu": 2}[route])
+        gpu.spmm_plan_set_route(plan, {"auto": 0, "mfma": 1, "valu": 2, "class": 3}[route])
         Cd = torch.full((A.M, N), float("nan"), dtype=torch.float32, device="cuda")
         gpu.spmm_exec(plan, Bd, Cd)
         torch.cuda.synchronize()
@@ -67,7 +67,7 @@ def test_config2_clustered(gpu):
 
 def test_config3_powerlaw(gpu):
     A, Ns = W.config(3)
-    check_full(gpu, A, Ns[0], "config3", routes=("auto", "mfma"))
+    check_full(gpu, A, Ns[0], "config3", routes=("auto", "class"))
 
 
 @pytest.mark.parametrize("fill", [0.05, 0.2, 0.8])

@@ -104,7 +104,7 @@ def test_product_all_routes(gpu, name, N):
     B = W.dense_b(A.K, N, 77)
     Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
     plan = make_plan(gpu, A)
-    for route in (gpu.ROUTE_AUTO, gpu.ROUTE_MFMA, gpu.ROUTE_VALU):
+    for route in (gpu.ROUTE_AUTO, gpu.ROUTE_CLASS, gpu.ROUTE_VALU):
         print(f"case {name} N={N} route={route}", flush=True)
         Cg = run_product(gpu, plan, A, B, route=route)
         assert not np.isnan(Cg).any(), "every element of C must be written"
@@ -245,5 +245,5 @@ def test_config1_tiny_banded_full(gpu):
     for N in Ns + [128]:
         B = W.dense_b(A.K, N, 1001)
         Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
-        for route in (gpu.ROUTE_AUTO, gpu.ROUTE_MFMA, gpu.ROUTE_VALU):
+        for route in (gpu.ROUTE_AUTO, gpu.ROUTE_CLASS, gpu.ROUTE_VALU):
             check_c(run_product(gpu, plan, A, B, route=route), Cref, S)
