@@ -316,9 +316,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     uint64_t st_mask[R];
     float st_a[R];
     float st_b[R][T];
+    // Each lane needs the packed value whose index is the number of pattern bits below its
+    // own bit (the prefix-count decode of Algorithm 1), or zero if its bit is clear.  Wide
+    // tiles fetch it with a per-lane gather in flight with the B rows.  For narrow tiles the
+    // vector-memory pipe is the bottleneck, and a gather costs it as much as a dwordx4 load:
+    // there the values are fetched coalesced (lane l reads value l; lanes past the brick's
+    // count read neighbouring, valid memory) and compute() picks across lanes.
+    constexpr bool kCoalescedValues = T <= 2;
     auto issue = [&](uint64_t mask, uint32_t off, uint32_t ro, int s) {
       st_mask[s] = mask;
-      st_a[s] = vals[(int64_t)off + __popcll(mask & below)];
+      st_a[s] = vals[(int64_t)off + (kCoalescedValues ? lane : __popcll(mask & below))];
 #pragma unroll
       for (int q = 0; q < NV; ++q) {
         float tmp[V];
@@ -328,7 +335,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
       }
     };
     auto compute = [&](int s) {
-      const float a = ((st_mask[s] >> bit) & 1ull) ? st_a[s] : 0.f;
+      const uint64_t m = st_mask[s];
+      float got = st_a[s];
+      if constexpr (kCoalescedValues)
+        got = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
+                                            4 * __popcll(m & below), __builtin_bit_cast(int, got)));
+      const float a = ((m >> bit) & 1ull) ? got : 0.f;
 #pragma unroll
       for (int u = 0; u < T; ++u)
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, st_b[s][u], acc[u], 0, 0, 0);
