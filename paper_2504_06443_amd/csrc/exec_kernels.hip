@@ -480,6 +480,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu(
 
 // ------------------------------------------------------------------ merge (a8)
 // Sum the partial 16 x N tiles of a split panel in part order and store to C.
+// One workgroup per split panel; VEC floats per thread per step.
+template <int VEC>
 __global__ __launch_bounds__(256) void k_merge(const MergeItem* __restrict__ items,
                                                const float* __restrict__ partial,
                                                float* __restrict__ C, int64_t M, int64_t N) {
@@ -487,10 +489,18 @@ __global__ __launch_bounds__(256) void k_merge(const MergeItem* __restrict__ ite
   const int64_t row0 = (int64_t)it.panel * kPanel;
   const int64_t rows = min<int64_t>(kPanel, M - row0);
   const int64_t tile = (int64_t)kPanel * N;
-  for (int64_t x = threadIdx.x; x < rows * N; x += blockDim.x) {
-    float s = 0.f;
-    for (uint32_t q = 0; q < it.nparts; ++q) s += partial[((int64_t)it.slot_begin + q) * tile + x];
-    C[row0 * N + x] = s;
+  const float* src = partial + (int64_t)it.slot_begin * tile;
+  float* dst = C + row0 * N;
+  for (int64_t x = (int64_t)threadIdx.x * VEC; x < rows * N; x += (int64_t)blockDim.x * VEC) {
+    float s[VEC];
+    load_vec<VEC>(src + x, s);
+    for (uint32_t q = 1; q < it.nparts; ++q) {
+      float t[VEC];
+      load_vec<VEC>(src + (int64_t)q * tile + x, t);
+#pragma unroll
+      for (int w = 0; w < VEC; ++w) s[w] += t[w];
+    }
+    store_vec<VEC>(dst + x, s);
   }
 }
 
@@ -586,7 +596,11 @@ hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const 
 hipError_t launch_merge(const MergeItem* items, int64_t n_items, const float* partial, float* C,
                         int64_t M, int64_t N, hipStream_t s) {
   if (n_items == 0 || N == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_merge, dim3((unsigned)n_items), dim3(256), 0, s, items, partial, C, M, N);
+  // rows * N is a multiple of 4 whenever N is, so whole vectors never straddle the end
+  if (N % 4 == 0 && ptr_aligned16(partial) && ptr_aligned16(C))
+    hipLaunchKernelGGL(k_merge<4>, dim3((unsigned)n_items), dim3(256), 0, s, items, partial, C, M, N);
+  else
+    hipLaunchKernelGGL(k_merge<1>, dim3((unsigned)n_items), dim3(256), 0, s, items, partial, C, M, N);
   return hipGetLastError();
 }
 

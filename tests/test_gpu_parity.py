@@ -247,3 +247,79 @@ def test_config1_tiny_banded_full(gpu):
         Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
         for route in (gpu.ROUTE_AUTO, gpu.ROUTE_CLASS, gpu.ROUTE_VALU):
             check_c(run_product(gpu, plan, A, B, route=route), Cref, S)
+
+
+def test_exec_on_side_stream_and_graph_replay(gpu):
+    """spmm_exec only enqueues work once an N's work list is cached: it can run on a
+    non-default stream and be captured in a HIP graph; every replay must reproduce
+    the eager result bit for bit (also for a matrix with split panels and both kernels)."""
+    import torch
+    # upper half: dense 3x3 blocks (Medium class -> MFMA kernel, split in two by force);
+    # lower half: scattered power-law rows (Low class -> CSR kernel)
+    top = W.clustered_blocks(1536, 6, 90, seed=50)
+    low = W.power_law(M=1500, target_nnz=None, cap=300, seed=51)
+    rows = np.concatenate([np.repeat(np.arange(top.M), np.diff(top.rowptr)),
+                           top.M + np.repeat(np.arange(low.M), np.diff(low.rowptr))])
+    cols = np.concatenate([top.colind, low.colind])
+    A = W.csr_from_coo(top.M + low.M, max(top.K, low.K), rows, cols,
+                       np.concatenate([top.vals, low.vals]))
+    N = 128
+    plan = make_plan(gpu, A)
+    gpu.spmm_plan_set_route(plan, gpu.ROUTE_CLASS)
+    gpu.spmm_plan_set_split(plan, 2)
+    B1 = torch.from_numpy(W.dense_b(A.K, N, 1)).cuda()
+    B2 = torch.from_numpy(W.dense_b(A.K, N, 2)).cuda()
+    eager1 = gpu.spmm_exec(plan, B1).clone()          # also caches the work list for N
+    eager2 = gpu.spmm_exec(plan, B2).clone()
+    torch.cuda.synchronize()
+    wl = gpu.spmm_plan_worklist(plan, N)
+    assert wl["n_split_panels"] > 0 and wl["n_valu_panels"] > 0 and wl["n_mfma_items"] > 0
+
+    side = torch.cuda.Stream()
+    Bs = B1.clone()
+    Cs = torch.empty_like(eager1)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gpu.spmm_exec(plan, Bs, Cs)                   # uses the current (side) stream
+    side.synchronize()
+    assert torch.equal(Cs, eager1)
+
+    graph = torch.cuda.CUDAGraph()
+    Cs.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        gpu.spmm_exec(plan, Bs, Cs)
+    for k, (src, expect) in enumerate([(B1, eager1), (B2, eager2), (B1, eager1), (B2, eager2)]):
+        Bs.copy_(src)
+        Cs.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Cs, expect), f"replay {k}"
+
+
+def test_error_paths_on_device(gpu):
+    import ctypes
+    import torch
+    A = W.uniform_random(40, 30, 0.2, 1)
+    plan = make_plan(gpu, A)
+    B = torch.zeros((30, 8), device="cuda")
+    C = torch.zeros((40, 8), device="cuda")
+    lib = gpu._lib
+    assert lib.spmm_exec(plan._h, ctypes.c_void_p(B.data_ptr()), -1, ctypes.c_void_p(C.data_ptr()), None) == gpu.SPMM_EINVAL
+    assert lib.spmm_exec(plan._h, ctypes.c_void_p(B.data_ptr()), 8, None, None) == gpu.SPMM_EINVAL
+    assert lib.spmm_exec(plan._h, None, 8, ctypes.c_void_p(C.data_ptr()), None) == gpu.SPMM_EINVAL
+    assert "NULL" in gpu.spmm_last_error()
+    assert lib.spmm_plan_set_route(plan._h, 7) == gpu.SPMM_EINVAL
+    assert lib.spmm_plan_set_split(plan._h, -2) == gpu.SPMM_EINVAL
+    with pytest.raises(ValueError):
+        gpu.spmm_exec(plan, torch.zeros((31, 8), device="cuda"))
+    # nnz that disagrees with rowptr[M]
+    rp, ci, v = to_dev(A)
+    out = ctypes.c_void_p()
+    st = lib.spmm_plan(A.M, A.K, A.nnz - 1, ctypes.c_void_p(rp.data_ptr()), ctypes.c_void_p(ci.data_ptr()),
+                       ctypes.c_void_p(v.data_ptr()), None, ctypes.byref(out))
+    assert st == gpu.SPMM_EFORMAT and not out.value
+    # the plan is still usable
+    gpu.spmm_exec(plan, B, C)
+    torch.cuda.synchronize()
