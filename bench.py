@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
+L2_PEAK_GBS = 128 * 64 * 2.3   # derived: 8 XCDs x 16 channels x 64 B/clk x 2.3 GHz (measured clock)
 
 WORKLOADS = {
     # name: (config index, kwargs, default N)
@@ -180,6 +181,11 @@ def main():
     roof_mfma = {"bound": "mfma", "achieved": mfma_achieved, "peak": MFMA_FP32_PEAK_TFLOPS,
                  "unit": "TFLOP/s", "frac": mfma_achieved / MFMA_FP32_PEAK_TFLOPS,
                  "traffic": None}
+    # third ceiling, not one of the published peaks: every panel pulls its B rows through the
+    # XCD's L2 (bytes_noreuse); 128 L2 channels x 64 B/clk x 2.3 GHz = 18.8 TB/s
+    l2_achieved = syn["bytes_noreuse"] / (kernel_ms * 1e-3) / 1e9
+    roof_l2 = {"bound": "l2", "achieved": l2_achieved, "peak": L2_PEAK_GBS, "unit": "GB/s",
+               "frac": l2_achieved / L2_PEAK_GBS, "traffic": None}
     mfma_binds = wl["n_mfma_items"] > 0 and syn["roof_gflops_mfma"] < syn["roof_gflops_hbm"]
     roofline = roof_mfma if mfma_binds else roof_hbm
     traffic_file = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_N{N}.txt")
@@ -219,6 +225,7 @@ def main():
         "roofline": roofline,
         "roofline_hbm": roof_hbm,
         "roofline_mfma": roof_mfma,
+        "roofline_l2": roof_l2,
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(A, Bs[0].cpu().numpy())
