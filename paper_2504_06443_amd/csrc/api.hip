@@ -89,15 +89,29 @@ struct spmm_plan {
     for (auto& kv : lists) delete kv.second;
     lists.clear();
   }
+  // the arrays above are carved out of two device allocations
+  char* fixed_arena = nullptr;   // panel_ptr, rowptr, colind, csr_vals
+  char* brick_arena = nullptr;   // brick_cols, brick_mask, brick_valptr, vals
   ~spmm_plan() {
     drop_lists();
-    void* bufs[] = {panel_ptr, brick_cols, brick_mask, brick_valptr, vals, rowptr, colind, csr_vals};
-    for (void* b : bufs)
-      if (b) (void)hipFree(b);
+    if (fixed_arena) (void)hipFree(fixed_arena);
+    if (brick_arena) (void)hipFree(brick_arena);
   }
 };
 
 namespace {
+
+// Bump allocator over one device allocation; sub-arrays are 256-byte aligned.
+struct Arena {
+  char* base = nullptr;
+  size_t used = 0, cap = 0;
+  static size_t pad(size_t bytes) { return (bytes + 255) & ~size_t(255); }
+  template <typename T> T* take(int64_t n) {
+    T* p = reinterpret_cast<T*>(base + used);
+    used += pad((size_t)std::max<int64_t>(n, 1) * sizeof(T));
+    return used <= cap ? p : nullptr;
+  }
+};
 
 template <typename T>
 hipError_t dev_alloc(T** p, int64_t n) {
@@ -265,43 +279,58 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   const int64_t P = (M + kPanel - 1) / kPanel;
   pl->M = M; pl->K = K; pl->nnz = nnz; pl->P = P;
 
-  // scratch (freed before returning)
-  uint32_t* d_err = nullptr;
-  uint32_t* ent_row = nullptr;
-  uint8_t* first = nullptr;
-  uint32_t* first_scan = nullptr;
-  uint32_t* scan_tmp = nullptr;
-  uint32_t* nbricks_p = nullptr;
-  uint32_t* panel_nnzptr = nullptr;
-  uint32_t* ent_brick = nullptr;
-  uint8_t* ent_bit = nullptr;
-  uint8_t* col_seen = nullptr;
-  uint8_t* panel_class = nullptr;
-  unsigned long long* counters = nullptr;
+  // Device memory comes from three allocations: scratch (freed before returning), the plan's
+  // fixed-size arrays, and the brick arrays once their count is known.  Sub-arrays are
+  // 256-byte aligned.
+  auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
+  Arena scratch, fixed, bricks;
+  uint32_t *d_err, *ent_row, *first_scan, *scan_tmp, *nbricks_p, *panel_nnzptr, *ent_brick;
+  uint8_t *first, *ent_bit, *col_seen, *panel_class;
+  unsigned long long* counters;
   uint32_t h_err = 0, h_nb = 0, h_active = 0;
+  const int64_t scan_elems = (int64_t)scan_tmp_elems(std::max(nnz, P + 1));  // bricks <= nnz
 
-  {
-    hipDeviceProp_t prop;
-    HIP_TRY(hipGetDevice(&pl->device));
-    HIP_TRY(hipGetDeviceProperties(&prop, pl->device));
-    pl->num_cus = std::max(1, prop.multiProcessorCount);
-  }
+  HIP_TRY(hipGetDevice(&pl->device));
+  HIP_TRY(hipDeviceGetAttribute(&pl->num_cus, hipDeviceAttributeMultiprocessorCount, pl->device));
+  pl->num_cus = std::max(1, pl->num_cus);
 
-  // ---- validation (device), before anything trusts the indices
-  HIP_TRY(dev_alloc(&d_err, 1));
+  scratch.cap = need(1, 4) + need(nnz, 4) + need(nnz, 1) + need(nnz + 1, 4) + need(scan_elems, 4) +
+                need(P, 4) + need(P + 1, 4) + need(nnz, 4) + need(nnz, 1) + need(K, 1) + need(P, 1) +
+                need(kNumCounters, 8);
+  HIP_TRY(hipMalloc((void**)&scratch.base, scratch.cap));
+  d_err = scratch.take<uint32_t>(1);
+  ent_row = scratch.take<uint32_t>(nnz);
+  first = scratch.take<uint8_t>(nnz);
+  first_scan = scratch.take<uint32_t>(nnz + 1);
+  scan_tmp = scratch.take<uint32_t>(scan_elems);
+  nbricks_p = scratch.take<uint32_t>(P);
+  panel_nnzptr = scratch.take<uint32_t>(P + 1);
+  ent_brick = scratch.take<uint32_t>(nnz);
+  ent_bit = scratch.take<uint8_t>(nnz);
+  col_seen = scratch.take<uint8_t>(K);
+  panel_class = scratch.take<uint8_t>(P);
+  counters = scratch.take<unsigned long long>(kNumCounters);
+
+  fixed.cap = need(P + 1, 4) + need(M + 1, 4) + need(nnz, 4) + need(nnz, 4);
+  HIP_TRY(hipMalloc((void**)&fixed.base, fixed.cap));
+  pl->fixed_arena = fixed.base;
+  pl->panel_ptr = fixed.take<uint32_t>(P + 1);
+  pl->rowptr = fixed.take<int32_t>(M + 1);
+  pl->colind = fixed.take<int32_t>(nnz);
+  pl->csr_vals = fixed.take<float>(nnz);
+
+  // ---- validation (device), before anything trusts the indices.  The column check only
+  // dereferences rowptr[0..M] and colind[0..nnz), so it is safe to run on an invalid rowptr.
   HIP_TRY(hipMemsetAsync(d_err, 0, sizeof(uint32_t), s));
   HIP_TRY(launch_validate_rowptr(rowptr, M, nnz, d_err, s));
+  HIP_TRY(launch_validate_cols(rowptr, colind, M, K, nnz, ent_row, d_err, s));
   HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
-  if (h_err) {
+  if (h_err & (kErrRowptrEnds | kErrRowptrOrder)) {
     status = fail(SPMM_EFORMAT, "invalid rowptr (%s)",
                   (h_err & kErrRowptrEnds) ? "rowptr[0] != 0 or rowptr[M] != nnz" : "not monotone");
     goto done;
   }
-  HIP_TRY(dev_alloc(&ent_row, nnz));
-  HIP_TRY(launch_validate_cols(rowptr, colind, M, K, nnz, ent_row, d_err, s));
-  HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
   if (h_err) {
     status = fail(SPMM_EFORMAT, "invalid colind (%s)",
                   (h_err & kErrColRange) ? "column out of range"
@@ -310,70 +339,15 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   }
 
   // ---- a1: first occurrence of each column in its panel, scanned
-  HIP_TRY(dev_alloc(&first, nnz));
-  HIP_TRY(dev_alloc(&first_scan, nnz + 1));
-  HIP_TRY(dev_alloc(&scan_tmp, (int64_t)scan_tmp_elems(std::max(nnz, P + 1))));
   HIP_TRY(launch_first_in_panel(rowptr, colind, ent_row, nnz, first, s));
   HIP_TRY(launch_scan_u8(first, nnz, first_scan, scan_tmp, s));
 
   // ---- a2: bricks per panel -> panel_ptr
-  HIP_TRY(dev_alloc(&nbricks_p, P));
-  HIP_TRY(dev_alloc(&panel_nnzptr, P + 1));
-  HIP_TRY(dev_alloc(&pl->panel_ptr, P + 1));
   HIP_TRY(launch_panel_counts(rowptr, first_scan, M, P, nbricks_p, panel_nnzptr, s));
   HIP_TRY(launch_scan_u32(nbricks_p, P, pl->panel_ptr, scan_tmp, s));
   HIP_TRY(hipMemcpyAsync(&h_nb, pl->panel_ptr + P, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipMemcpyAsync(&h_active, first_scan + nnz, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  pl->nb = h_nb;
-  pl->n_active_cols = h_active;
-  if ((int64_t)h_nb * kBrickK >= (int64_t(1) << 32)) {
-    status = fail(SPMM_ELIMIT, "4 * bricks must be below 2^32");
-    goto done;
-  }
-
-  // ---- a2/a3: brick columns and patterns
-  // spare entries past the end of each array (see BrickFormat)
-  HIP_TRY(dev_alloc(&pl->brick_cols, (pl->nb + kFormatPad) * kBrickK));
-  HIP_TRY(dev_alloc(&pl->brick_mask, pl->nb + kFormatPad));
-  HIP_TRY(dev_alloc(&pl->brick_valptr, pl->nb + 1 + kFormatPad));
-  HIP_TRY(dev_alloc(&pl->vals, nnz + 64));
-  HIP_TRY(hipMemsetAsync(pl->brick_cols + pl->nb * kBrickK, 0, kFormatPad * kBrickK * 4, s));
-  HIP_TRY(hipMemsetAsync(pl->brick_mask + pl->nb, 0, kFormatPad * 8, s));
-  HIP_TRY(launch_fill_u32(pl->brick_valptr + pl->nb + 1, kFormatPad, (uint32_t)nnz, s));
-  HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, 64 * sizeof(float), s));
-  HIP_TRY(dev_alloc(&ent_brick, nnz));
-  HIP_TRY(dev_alloc(&ent_bit, nnz));
-  HIP_TRY(dev_alloc(&col_seen, K));
-  HIP_TRY(launch_fill_u32(pl->brick_cols, pl->nb * kBrickK, kPadCol, s));
-  HIP_TRY(launch_fill_u64(pl->brick_mask, pl->nb, 0ull, s));
-  HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
-  HIP_TRY(launch_rank_scatter(rowptr, colind, ent_row, first, first_scan, pl->panel_ptr, M, nnz,
-                              pl->brick_cols, pl->brick_mask, ent_brick, ent_bit, col_seen, s));
-
-  // ---- a4: value offsets and packed values
-  if ((int64_t)scan_tmp_elems(pl->nb) > (int64_t)scan_tmp_elems(std::max(nnz, P + 1))) {
-    HIP_TRY(hipStreamSynchronize(s));
-    HIP_TRY(hipFree(scan_tmp));
-    scan_tmp = nullptr;
-    HIP_TRY(dev_alloc(&scan_tmp, (int64_t)scan_tmp_elems(pl->nb)));
-  }
-  HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
-  HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
-                             pl->vals, s));
-
-  // ---- a5: per-panel classes and the synergy counts
-  HIP_TRY(dev_alloc(&panel_class, P));
-  HIP_TRY(dev_alloc(&counters, kNumCounters));
-  HIP_TRY(hipMemsetAsync(counters, 0, kNumCounters * sizeof(unsigned long long), s));
-  HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
-  HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
-  HIP_TRY(launch_count_flags(col_seen, K, counters + kCntDistinctCols, s));
-
-  // ---- plan-owned CSR copy for the vector-ALU kernel
-  HIP_TRY(dev_alloc(&pl->rowptr, M + 1));
-  HIP_TRY(dev_alloc(&pl->colind, nnz));
-  HIP_TRY(dev_alloc(&pl->csr_vals, nnz));
+  // plan-owned CSR copy for the vector-ALU kernel, while the host waits for the counts
   HIP_TRY(hipMemcpyAsync(pl->rowptr, rowptr, (size_t)(M + 1) * sizeof(int32_t),
                          hipMemcpyDeviceToDevice, s));
   if (nnz > 0) {
@@ -382,6 +356,42 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
     HIP_TRY(hipMemcpyAsync(pl->csr_vals, vals, (size_t)nnz * sizeof(float),
                            hipMemcpyDeviceToDevice, s));
   }
+  HIP_TRY(hipStreamSynchronize(s));
+  pl->nb = h_nb;
+  pl->n_active_cols = h_active;
+  if ((int64_t)h_nb * kBrickK >= (int64_t(1) << 32)) {
+    status = fail(SPMM_ELIMIT, "4 * bricks must be below 2^32");
+    goto done;
+  }
+
+  // ---- a2/a3: brick columns and patterns (arrays carry spare entries, see BrickFormat)
+  bricks.cap = need((pl->nb + kFormatPad) * kBrickK, 4) + need(pl->nb + kFormatPad, 8) +
+               need(pl->nb + 1 + kFormatPad, 4) + need(nnz + 64, 4);
+  HIP_TRY(hipMalloc((void**)&bricks.base, bricks.cap));
+  pl->brick_arena = bricks.base;
+  pl->brick_cols = bricks.take<uint32_t>((pl->nb + kFormatPad) * kBrickK);
+  pl->brick_mask = bricks.take<uint64_t>(pl->nb + kFormatPad);
+  pl->brick_valptr = bricks.take<uint32_t>(pl->nb + 1 + kFormatPad);
+  pl->vals = bricks.take<float>(nnz + 64);
+  HIP_TRY(launch_fill_u32(pl->brick_cols, pl->nb * kBrickK, kPadCol, s));
+  HIP_TRY(hipMemsetAsync(pl->brick_cols + pl->nb * kBrickK, 0, kFormatPad * kBrickK * 4, s));
+  HIP_TRY(hipMemsetAsync(pl->brick_mask, 0, (size_t)(pl->nb + kFormatPad) * 8, s));
+  HIP_TRY(launch_fill_u32(pl->brick_valptr + pl->nb + 1, kFormatPad, (uint32_t)nnz, s));
+  HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, 64 * sizeof(float), s));
+  HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
+  HIP_TRY(launch_rank_scatter(rowptr, colind, ent_row, first, first_scan, pl->panel_ptr, M, nnz,
+                              pl->brick_cols, pl->brick_mask, ent_brick, ent_bit, col_seen, s));
+
+  // ---- a4: value offsets and packed values
+  HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
+  HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
+                             pl->vals, s));
+
+  // ---- a5: per-panel classes and the synergy counts
+  HIP_TRY(hipMemsetAsync(counters, 0, kNumCounters * sizeof(unsigned long long), s));
+  HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
+  HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
+  HIP_TRY(launch_count_flags(col_seen, K, counters + kCntDistinctCols, s));
 
   // ---- host copies for the work-list builder and the model
   try {
@@ -405,12 +415,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
 
 done:
   if (status != SPMM_OK) (void)hipStreamSynchronize(s);
-  {
-    void* scratch[] = {d_err, ent_row, first, first_scan, scan_tmp, nbricks_p, panel_nnzptr,
-                       ent_brick, ent_bit, col_seen, panel_class, counters};
-    for (void* b : scratch)
-      if (b) (void)hipFree(b);
-  }
+  if (scratch.base) (void)hipFree(scratch.base);
   if (status != SPMM_OK) {
     delete pl;
     return status;
