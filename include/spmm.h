@@ -145,7 +145,8 @@ int spmm_plan_export(const spmm_plan_t *plan, uint32_t *panel_ptr /* host [P+1] 
  *
  * spmm_plan_set_route: which kernel handles which panel (enum spmm_route).
  * spmm_plan_set_split: how heavy panels are split along K into virtual panels:
- *   parts = 0  Eq. 6-7: parts_p = round( blocks_p / avg_blocks / num_waves ), at least 1,
+ *   parts = 0  Eq. 6-7: ratio_p = blocks_p / avg_blocks / num_waves; parts_p = 1 while
+ *              ratio_p < 2, else round(ratio_p);
  *              num_waves = ceil(work items / (CUs * resident waves per CU))
  *   parts = 1  never split
  *   parts > 1  split every panel that has at least `parts` blocks into `parts`

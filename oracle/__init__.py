@@ -166,8 +166,9 @@ def partition_counts(nbricks_per_panel, total_work_items: int, num_cus: int,
     num_waves = ceil(total_work_items / (num_cus * resident_per_cu)), at least 1;
     num_loads_p = blocks_p / average blocks over all panels (Eq. 6);
     partition_ratio_p = num_loads_p / num_waves (Eq. 7);
-    parts_p = max(1, round-half-up(partition_ratio_p)), evaluated in integers
-    (the paper gives no rounding rule: a ratio of exactly 1 must not split).
+    parts_p = 1 if partition_ratio_p < 2, else round-half-up(partition_ratio_p),
+    evaluated in integers (the paper gives no rounding rule: a ratio of exactly 1
+    must not split; a panel is split once it carries two wave-adjusted average loads).
     Returns (parts list, num_waves)."""
     blocks = [_ceil_div(int(b), 4) for b in nbricks_per_panel]
     P = len(blocks)
@@ -178,7 +179,8 @@ def partition_counts(nbricks_per_panel, total_work_items: int, num_cus: int,
         if total == 0 or b == 0:
             parts.append(1)
         else:
-            parts.append(max(1, (2 * b * P + total * waves) // (2 * total * waves)))
+            num, den = b * P, total * waves          # partition_ratio = num / den
+            parts.append(1 if num < 2 * den else (2 * num + den) // (2 * den))
     return parts, waves
 
 

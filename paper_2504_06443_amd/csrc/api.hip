@@ -127,8 +127,8 @@ int classify(int64_t nnz, int64_t nb) {
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Eq. 6-7 in integers: partition_ratio_p = blocks_p * P / (total_blocks * waves), rounded to
-// the nearest integer (halves up), at least 1.
+// Eq. 6-7 in integers: partition_ratio_p = blocks_p * P / (total_blocks * waves); a panel is
+// split once the ratio reaches 2, into round-half-up(ratio) parts.
 void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, int64_t capacity,
                       uint32_t* parts, int64_t* waves_out) {
   int64_t total = 0;
@@ -141,7 +141,7 @@ void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, in
       // blocks * P can exceed 2^63 only for absurd sizes; use 128-bit to be safe
       const __int128 num = (__int128)blocks * P;
       const __int128 den = (__int128)total * waves;
-      q = (int64_t)((2 * num + den) / (2 * den));
+      q = num < 2 * den ? 1 : (int64_t)((2 * num + den) / (2 * den));
     }
     parts[p] = (uint32_t)std::max<int64_t>(1, q);
   }

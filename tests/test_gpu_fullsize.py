@@ -81,3 +81,36 @@ def test_config4_fem(gpu):
     A, Ns = W.config(4)
     for N in Ns:
         check_full(gpu, A, N, "config4", check_format=(N == Ns[0]))
+
+
+def test_b_larger_than_4gib_uses_64bit_offsets(gpu):
+    """B of 4.4 GB: byte offsets into B no longer fit 32 bits, which must switch the
+    library to its 64-bit addressing kernel; rows at both ends of B are referenced."""
+    import torch
+    K, N, M = 1 << 21, 520, 4096
+    rng = np.random.default_rng(7)
+    per_row = 24
+    rows = np.repeat(np.arange(M), per_row)
+    cols = np.concatenate([rng.integers(0, K, size=M * per_row - 64),
+                           np.arange(K - 32, K), np.arange(0, 32)])
+    A = W.csr_from_coo(M, K, rows, cols, rng.uniform(-1, 1, size=rows.size).astype(np.float32))
+    assert 4 * K * N >= 1 << 32
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    Bd = torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32)
+    plan = make_plan(gpu, A)
+    for route in (gpu.ROUTE_AUTO, gpu.ROUTE_VALU):
+        gpu.spmm_plan_set_route(plan, route)
+        Cd = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        gpu.spmm_exec(plan, Bd, Cd)
+        torch.cuda.synchronize()
+        assert not torch.isnan(Cd).any().item()
+        sample = np.unique(np.concatenate([rng.integers(0, M, 64), [0, M - 1]]))
+        # the oracle only needs the B rows these sampled rows touch: remap columns to a small B
+        ent = np.concatenate([np.arange(A.rowptr[i], A.rowptr[i + 1]) for i in sample])
+        used, inv = np.unique(A.colind[ent], return_inverse=True)
+        Bsmall = Bd[torch.from_numpy(used.astype(np.int64)).cuda()].cpu().numpy()
+        rp = np.zeros(len(sample) + 1, np.int32)
+        rp[1:] = np.cumsum([A.rowptr[i + 1] - A.rowptr[i] for i in sample])
+        Cref, S = oracle.spmm_f64(rp, inv.astype(np.int32), A.vals[ent], Bsmall)
+        Cg = Cd[torch.from_numpy(sample).cuda()].cpu().numpy().astype(np.float64)
+        assert (np.abs(Cg - Cref) / S).max() <= TOL, route

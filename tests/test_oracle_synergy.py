@@ -152,7 +152,7 @@ def test_split_follows_eq6_eq7_exact_fractions():
         assert waves == w
         for p in range(P):
             ratio = blocks[p] / avg / w                     # Eq. 6 then Eq. 7
-            expect = max(1, int((ratio + Fraction(1, 2)) // 1))   # nearest, halves up
+            expect = 1 if ratio < 2 else int((ratio + Fraction(1, 2)) // 1)   # nearest, halves up
             assert parts[p] == expect
 
 
