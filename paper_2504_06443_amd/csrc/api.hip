@@ -160,7 +160,6 @@ int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** ou
   if (!wl) return fail(SPMM_ENOMEM, "host allocation failed");
   wl->N = N;
   const int tile = mfma_tile_for(std::max<int64_t>(N, 1));
-  const int V = tile >= 64 ? 4 : tile / 16;
   wl->info.n_tile = tile;
   wl->info.n_tiles = (int32_t)ceil_div(std::max<int64_t>(N, 1), tile);
 
@@ -189,7 +188,7 @@ int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** ou
   int64_t waves = 1;
   if (nm > 0) {
     if (pl->split == 0) {
-      const int resident = mfma_resident_waves_per_cu(tile, N % V == 0);
+      const int resident = mfma_resident_waves_per_cu(std::max<int64_t>(N, 1), pl->K);
       partition_counts(nm, nbricks.data(), nm * wl->info.n_tiles,
                        (int64_t)pl->num_cus * resident, parts.data(), &waves);
     } else if (pl->split > 1) {
@@ -285,6 +284,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
   Arena scratch, fixed, bricks;
   uint32_t *d_err, *ent_row, *first_scan, *scan_tmp, *nbricks_p, *panel_nnzptr, *ent_brick;
+  uint32_t *link, *first_list, *ent_rank;
   uint8_t *first, *ent_bit, *col_seen, *panel_class;
   unsigned long long* counters;
   uint32_t h_err = 0, h_nb = 0, h_active = 0;
@@ -296,7 +296,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
 
   scratch.cap = need(1, 4) + need(nnz, 4) + need(nnz, 1) + need(nnz + 1, 4) + need(scan_elems, 4) +
                 need(P, 4) + need(P + 1, 4) + need(nnz, 4) + need(nnz, 1) + need(K, 1) + need(P, 1) +
-                need(kNumCounters, 8);
+                need(kNumCounters, 8) + 3 * need(nnz, 4);
   HIP_TRY(hipMalloc((void**)&scratch.base, scratch.cap));
   d_err = scratch.take<uint32_t>(1);
   ent_row = scratch.take<uint32_t>(nnz);
@@ -310,6 +310,9 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   col_seen = scratch.take<uint8_t>(K);
   panel_class = scratch.take<uint8_t>(P);
   counters = scratch.take<unsigned long long>(kNumCounters);
+  link = scratch.take<uint32_t>(nnz);
+  first_list = scratch.take<uint32_t>(nnz);
+  ent_rank = scratch.take<uint32_t>(nnz);
 
   fixed.cap = need(P + 1, 4) + need(M + 1, 4) + need(nnz, 4) + need(nnz, 4);
   HIP_TRY(hipMalloc((void**)&fixed.base, fixed.cap));
@@ -339,8 +342,9 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   }
 
   // ---- a1: first occurrence of each column in its panel, scanned
-  HIP_TRY(launch_first_in_panel(rowptr, colind, ent_row, nnz, first, s));
+  HIP_TRY(launch_first_in_panel(rowptr, colind, ent_row, nnz, first, link, s));
   HIP_TRY(launch_scan_u8(first, nnz, first_scan, scan_tmp, s));
+  HIP_TRY(launch_compact_first(first, first_scan, nnz, first_list, s));
 
   // ---- a2: bricks per panel -> panel_ptr
   HIP_TRY(launch_panel_counts(rowptr, first_scan, M, P, nbricks_p, panel_nnzptr, s));
@@ -379,8 +383,10 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(launch_fill_u32(pl->brick_valptr + pl->nb + 1, kFormatPad, (uint32_t)nnz, s));
   HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, 64 * sizeof(float), s));
   HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
-  HIP_TRY(launch_rank_scatter(rowptr, colind, ent_row, first, first_scan, pl->panel_ptr, M, nnz,
-                              pl->brick_cols, pl->brick_mask, ent_brick, ent_bit, col_seen, s));
+  HIP_TRY(launch_rank_first(rowptr, colind, ent_row, first_list, first_scan, pl->panel_ptr, M,
+                            pl->n_active_cols, ent_rank, pl->brick_cols, s));
+  HIP_TRY(launch_scatter_bits(colind, ent_row, link, ent_rank, pl->panel_ptr, nnz, pl->brick_mask,
+                              ent_brick, ent_bit, col_seen, s));
 
   // ---- a4: value offsets and packed values
   HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));

@@ -30,6 +30,8 @@
 
 namespace spmm {
 
+int mfma_tile_for(int64_t N) { return N <= 16 ? 16 : (N <= 32 ? 32 : (N <= 64 ? 64 : 128)); }
+
 namespace {
 
 typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -525,14 +527,41 @@ int occupancy_t() {
   return nb * kWavesPerBlock;
 }
 
+template <int T>
+int occupancy_fast_t() {
+  int nb = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_spmm_mfma_fast<T>, 64 * kWavesPerBlock,
+                                                   0) != hipSuccess || nb < 1)
+    nb = 1;
+  return nb * kWavesPerBlock;
+}
+
 bool ptr_aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// the fast kernel serves N that is a multiple of the vector width with B below 4 GiB
+bool fast_path_shape(int64_t N, int64_t K) {
+  const int tile = mfma_tile_for(N);
+  const int V = tile >= 64 ? 4 : tile / 16;
+  return N % V == 0 && K > 0 && (double)K * (double)N * 4.0 < 4294967296.0;
+}
 
 }  // namespace
 
-int mfma_tile_for(int64_t N) { return N <= 16 ? 16 : (N <= 32 ? 32 : (N <= 64 ? 64 : 128)); }
-
-int mfma_resident_waves_per_cu(int n_tile, bool aligned) {
-  switch (n_tile) {
+// Wavefronts of the MFMA kernel that fit on one CU at a time, for the kernel variant that
+// (N, K) selects when the operands are 16-byte aligned: the "thread blocks per SM" of Eq. 7.
+int mfma_resident_waves_per_cu(int64_t N, int64_t K) {
+  const int tile = mfma_tile_for(N);
+  const int V = tile >= 64 ? 4 : tile / 16;
+  if (fast_path_shape(N, K)) {
+    switch (tile) {
+      case 16: return occupancy_fast_t<1>();
+      case 32: return occupancy_fast_t<2>();
+      case 64: return occupancy_fast_t<4>();
+      default: return occupancy_fast_t<8>();
+    }
+  }
+  const bool aligned = N % V == 0;
+  switch (tile) {
     case 16: return occupancy_t<1, true>();
     case 32: return aligned ? occupancy_t<2, true>() : occupancy_t<2, false>();
     case 64: return aligned ? occupancy_t<4, true>() : occupancy_t<4, false>();
@@ -548,7 +577,7 @@ hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t
   const int V = tile >= 64 ? 4 : tile / 16;
   const bool al = (N % V == 0) && ptr_aligned16(B) && ptr_aligned16(C) &&
                   (partial == nullptr || ptr_aligned16(partial));
-  if (al && K > 0 && (double)K * (double)N * 4.0 < 4294967296.0) {
+  if (al && fast_path_shape(N, K)) {
     unsigned gx = (unsigned)((n_items + kWavesPerBlock - 1) / kWavesPerBlock);
     gx = (gx + kXcds - 1) / kXcds * kXcds;  // whole rounds over the XCDs
     const dim3 grid(gx, (unsigned)((N + tile - 1) / tile)), block(64 * kWavesPerBlock);

@@ -9,7 +9,9 @@
 // sorted, so "is this the first row of the panel that holds column j" and
 // "how many distinct columns of the panel are smaller than j" are answered by
 // binary searches in the (at most 16) rows of the panel plus one exclusive scan
-// of the first-occurrence flags over the whole entry array.
+// of the first-occurrence flags over the whole entry array.  The second question
+// is only asked once per active column (the first-occurrence entries, compacted
+// into a list); the other entries of that column follow a link to it.
 #include "spmm_internal.h"
 
 #include <algorithm>
@@ -73,22 +75,33 @@ __global__ void k_validate_cols(const int32_t* __restrict__ rowptr,
 
 // ---------------------------------------------------------------- a1 census
 // first[e] = 1 iff no earlier row of the same panel stores column colind[e].
+// link[e] = the entry of that first row that stores the same column (e itself if first).
 __global__ void k_first_in_panel(const int32_t* __restrict__ rowptr,
                                  const int32_t* __restrict__ colind,
                                  const uint32_t* __restrict__ ent_row, int64_t nnz,
-                                 uint8_t* __restrict__ first) {
+                                 uint8_t* __restrict__ first, uint32_t* __restrict__ link) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= nnz) return;
   const int64_t i = ent_row[e];
   const int32_t j = colind[e];
   const int64_t r0 = i & ~(int64_t)(kPanel - 1);
   uint8_t f = 1;
-  for (int64_t r = r0; r < i; ++r) {
+  int64_t where = e;
+  for (int64_t r = r0; r < i; ++r) {  // rows in ascending order: the first hit is the first occurrence
     const int64_t s = rowptr[r], t = rowptr[r + 1];
     const int64_t pos = lower_bound_col(colind, s, t, j);
-    if (pos < t && colind[pos] == j) { f = 0; break; }
+    if (pos < t && colind[pos] == j) { f = 0; where = pos; break; }
   }
   first[e] = f;
+  link[e] = (uint32_t)where;
+}
+
+// first_list[k] = the k-th first-occurrence entry (k = exclusive scan of the flags)
+__global__ void k_compact_first(const uint8_t* __restrict__ first,
+                                const uint32_t* __restrict__ first_scan, int64_t nnz,
+                                uint32_t* __restrict__ first_list) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < nnz && first[e]) first_list[first_scan[e]] = (uint32_t)e;
 }
 
 // a2: bricks per panel and the entry offset of each panel.
@@ -114,19 +127,19 @@ __global__ void k_fill(T* __restrict__ p, int64_t n, T v) {
   if (i < n) p[i] = v;
 }
 
-// a2 + a3: rank of the entry's column among the panel's active columns, then
-// brick id, brick column and pattern bit 4*row + column.
-__global__ void k_rank_scatter(const int32_t* __restrict__ rowptr,
-                               const int32_t* __restrict__ colind,
-                               const uint32_t* __restrict__ ent_row,
-                               const uint8_t* __restrict__ first,
-                               const uint32_t* __restrict__ first_scan,
-                               const uint32_t* __restrict__ panel_ptr, int64_t M, int64_t nnz,
-                               uint32_t* __restrict__ brick_cols, uint64_t* brick_mask,
-                               uint32_t* __restrict__ ent_brick, uint8_t* __restrict__ ent_bit,
-                               uint8_t* __restrict__ col_seen) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= nnz) return;
+// a2: one thread per active column (= per first-occurrence entry): its rank among the
+// panel's active columns = number of first-occurrence entries of the panel with a smaller
+// column, counted row by row with one binary search and two reads of the scanned flags.
+__global__ void k_rank_first(const int32_t* __restrict__ rowptr,
+                             const int32_t* __restrict__ colind,
+                             const uint32_t* __restrict__ ent_row,
+                             const uint32_t* __restrict__ first_list,
+                             const uint32_t* __restrict__ first_scan,
+                             const uint32_t* __restrict__ panel_ptr, int64_t M, int64_t n_active,
+                             uint32_t* __restrict__ ent_rank, uint32_t* __restrict__ brick_cols) {
+  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n_active) return;
+  const int64_t e = first_list[k];
   const int64_t i = ent_row[e];
   const int32_t j = colind[e];
   const int64_t p = i / kPanel;
@@ -137,14 +150,30 @@ __global__ void k_rank_scatter(const int32_t* __restrict__ rowptr,
     const int64_t pos = (r == i) ? e : lower_bound_col(colind, s, t, j);
     rank += first_scan[pos] - first_scan[s];
   }
-  const uint32_t b = panel_ptr[p] + rank / kBrickK;
+  ent_rank[e] = rank;
+  brick_cols[(int64_t)panel_ptr[p] * kBrickK + rank] = (uint32_t)j;
+}
+
+// a3: every entry takes the rank of its column's first occurrence, which gives its brick,
+// its brick column and its pattern bit 4*row + column.
+__global__ void k_scatter_bits(const int32_t* __restrict__ colind,
+                               const uint32_t* __restrict__ ent_row,
+                               const uint32_t* __restrict__ link,
+                               const uint32_t* __restrict__ ent_rank,
+                               const uint32_t* __restrict__ panel_ptr, int64_t nnz,
+                               uint64_t* brick_mask, uint32_t* __restrict__ ent_brick,
+                               uint8_t* __restrict__ ent_bit, uint8_t* __restrict__ col_seen) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  const int64_t i = ent_row[e];
+  const uint32_t rank = ent_rank[link[e]];
+  const uint32_t b = panel_ptr[i / kPanel] + rank / kBrickK;
   const uint32_t c = rank % kBrickK;
-  const uint32_t bit = (uint32_t)(i - r0) * kBrickK + c;
+  const uint32_t bit = (uint32_t)(i % kPanel) * kBrickK + c;
   atomicOr((unsigned long long*)&brick_mask[b], 1ull << bit);
-  if (first[e]) brick_cols[(int64_t)b * kBrickK + c] = (uint32_t)j;
   ent_brick[e] = b;
   ent_bit[e] = (uint8_t)bit;
-  col_seen[j] = 1;
+  col_seen[colind[e]] = 1;
 }
 
 // a4: position of a value = start of its brick + set bits below its own bit.
@@ -340,10 +369,18 @@ hipError_t launch_validate_cols(const int32_t* rowptr, const int32_t* colind, in
 
 hipError_t launch_first_in_panel(const int32_t* rowptr, const int32_t* colind,
                                  const uint32_t* ent_row, int64_t nnz, uint8_t* first,
-                                 hipStream_t s) {
+                                 uint32_t* link, hipStream_t s) {
   if (nnz == 0) return hipSuccess;
   hipLaunchKernelGGL(k_first_in_panel, dim3(grid_for(nnz)), dim3(kThreads), 0, s, rowptr, colind,
-                     ent_row, nnz, first);
+                     ent_row, nnz, first, link);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_first(const uint8_t* first, const uint32_t* first_scan, int64_t nnz,
+                                uint32_t* first_list, hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_compact_first, dim3(grid_for(nnz)), dim3(kThreads), 0, s, first, first_scan,
+                     nnz, first_list);
   return hipGetLastError();
 }
 
@@ -367,16 +404,23 @@ hipError_t launch_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_rank_scatter(const int32_t* rowptr, const int32_t* colind,
-                               const uint32_t* ent_row, const uint8_t* first,
-                               const uint32_t* first_scan, const uint32_t* panel_ptr, int64_t M,
-                               int64_t nnz, uint32_t* brick_cols, uint64_t* brick_mask,
-                               uint32_t* ent_brick, uint8_t* ent_bit, uint8_t* col_seen,
-                               hipStream_t s) {
+hipError_t launch_rank_first(const int32_t* rowptr, const int32_t* colind, const uint32_t* ent_row,
+                             const uint32_t* first_list, const uint32_t* first_scan,
+                             const uint32_t* panel_ptr, int64_t M, int64_t n_active,
+                             uint32_t* ent_rank, uint32_t* brick_cols, hipStream_t s) {
+  if (n_active == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_rank_first, dim3(grid_for(n_active)), dim3(kThreads), 0, s, rowptr, colind,
+                     ent_row, first_list, first_scan, panel_ptr, M, n_active, ent_rank, brick_cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_bits(const int32_t* colind, const uint32_t* ent_row, const uint32_t* link,
+                               const uint32_t* ent_rank, const uint32_t* panel_ptr, int64_t nnz,
+                               uint64_t* brick_mask, uint32_t* ent_brick, uint8_t* ent_bit,
+                               uint8_t* col_seen, hipStream_t s) {
   if (nnz == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_rank_scatter, dim3(grid_for(nnz)), dim3(kThreads), 0, s, rowptr, colind,
-                     ent_row, first, first_scan, panel_ptr, M, nnz, brick_cols, brick_mask,
-                     ent_brick, ent_bit, col_seen);
+  hipLaunchKernelGGL(k_scatter_bits, dim3(grid_for(nnz)), dim3(kThreads), 0, s, colind, ent_row,
+                     link, ent_rank, panel_ptr, nnz, brick_mask, ent_brick, ent_bit, col_seen);
   return hipGetLastError();
 }
 

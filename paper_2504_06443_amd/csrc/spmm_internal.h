@@ -51,18 +51,22 @@ hipError_t launch_validate_cols(const int32_t* rowptr, const int32_t* colind, in
                                 int64_t nnz, uint32_t* ent_row, uint32_t* err, hipStream_t s);
 hipError_t launch_first_in_panel(const int32_t* rowptr, const int32_t* colind,
                                  const uint32_t* ent_row, int64_t nnz, uint8_t* first,
-                                 hipStream_t s);
+                                 uint32_t* link, hipStream_t s);
+hipError_t launch_compact_first(const uint8_t* first, const uint32_t* first_scan, int64_t nnz,
+                                uint32_t* first_list, hipStream_t s);
 hipError_t launch_panel_counts(const int32_t* rowptr, const uint32_t* first_scan, int64_t M,
                                int64_t P, uint32_t* nbricks_p, uint32_t* panel_nnzptr,
                                hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
 hipError_t launch_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
-hipError_t launch_rank_scatter(const int32_t* rowptr, const int32_t* colind,
-                               const uint32_t* ent_row, const uint8_t* first,
-                               const uint32_t* first_scan, const uint32_t* panel_ptr, int64_t M,
-                               int64_t nnz, uint32_t* brick_cols, uint64_t* brick_mask,
-                               uint32_t* ent_brick, uint8_t* ent_bit, uint8_t* col_seen,
-                               hipStream_t s);
+hipError_t launch_rank_first(const int32_t* rowptr, const int32_t* colind, const uint32_t* ent_row,
+                             const uint32_t* first_list, const uint32_t* first_scan,
+                             const uint32_t* panel_ptr, int64_t M, int64_t n_active,
+                             uint32_t* ent_rank, uint32_t* brick_cols, hipStream_t s);
+hipError_t launch_scatter_bits(const int32_t* colind, const uint32_t* ent_row, const uint32_t* link,
+                               const uint32_t* ent_rank, const uint32_t* panel_ptr, int64_t nnz,
+                               uint64_t* brick_mask, uint32_t* ent_brick, uint8_t* ent_bit,
+                               uint8_t* col_seen, hipStream_t s);
 hipError_t launch_pack_values(const float* vals, const uint32_t* ent_brick, const uint8_t* ent_bit,
                               const uint64_t* brick_mask, const uint32_t* brick_valptr,
                               int64_t nnz, float* packed, hipStream_t s);
@@ -95,7 +99,7 @@ struct BrickFormat {
 };
 
 int mfma_tile_for(int64_t N);   // columns of C per wavefront: 16, 32, 64 or 128
-int mfma_resident_waves_per_cu(int n_tile, bool aligned);
+int mfma_resident_waves_per_cu(int64_t N, int64_t K);
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
                             int64_t K, hipStream_t s);
