@@ -75,6 +75,23 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t *rowptr, const in
               const float *vals, void *stream, spmm_plan_t **out);
 
 /* ---------------------------------------------------------------------------
+ * spmm_plan_update_values -- new values for the same sparsity pattern (the use
+ * cases of Section 6, "Pre-processing Overheads": many products with one pattern,
+ * e.g. a matrix re-assembled every time step).  One gather/scatter kernel instead
+ * of a new plan.
+ *
+ *   vals    dev float[nnz], in the order of the colind array the plan was built
+ *           from; read by a kernel enqueued on `stream`, so it must stay valid
+ *           until that kernel has run
+ *
+ * Replaces the packed brick values and the plan's CSR copy; pattern, masks,
+ * offsets, synergy counts and work lists are unchanged (an entry whose new value
+ * is 0 stays a stored entry).  Enqueues only; allocates nothing.  Must not run
+ * concurrently with spmm_exec on the same plan.
+ */
+int spmm_plan_update_values(spmm_plan_t *plan, const float *vals, void *stream);
+
+/* ---------------------------------------------------------------------------
  * spmm_exec -- C = A . B (Section 3.1; Algorithm 1 re-designed for MFMA).
  *
  *   B   dev float[K*N], row-major, leading dimension N; must be finite (zero

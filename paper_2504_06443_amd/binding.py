@@ -29,7 +29,8 @@ ROUTE_AUTO, ROUTE_MFMA, ROUTE_VALU, ROUTE_CLASS = 0, 1, 2, 3
 CLASS_NAMES = ("Low", "Medium", "High")
 
 EXPORTED = (
-    "spmm_plan", "spmm_exec", "spmm_synergy", "spmm_plan_sizes", "spmm_plan_export",
+    "spmm_plan", "spmm_plan_update_values", "spmm_exec", "spmm_synergy", "spmm_plan_sizes",
+    "spmm_plan_export",
     "spmm_plan_set_route", "spmm_plan_set_split", "spmm_partition_counts",
     "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error",
 )
@@ -75,6 +76,7 @@ class _WorklistInfo(C.Structure):
 _vp = C.c_void_p
 _lib.spmm_last_error.restype = C.c_char_p
 _lib.spmm_plan.argtypes = [C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, C.POINTER(_vp)]
+_lib.spmm_plan_update_values.argtypes = [_vp, _vp, _vp]
 _lib.spmm_exec.argtypes = [_vp, _vp, C.c_int64, _vp, _vp]
 _lib.spmm_synergy.argtypes = [_vp, C.c_int64, C.POINTER(_Synergy)]
 _lib.spmm_plan_sizes.argtypes = [_vp, C.POINTER(_Sizes)]
@@ -132,6 +134,14 @@ def spmm_plan(M: int, K: int, rowptr, colind, vals, stream=None) -> Plan:
                           _dev(vals, torch.float32) if nnz else None,
                           _stream_ptr(stream), C.byref(out)))
     return Plan(out, M, K, nnz)
+
+
+def spmm_plan_update_values(plan: Plan, vals, stream=None):
+    """New values (device float32 [nnz], CSR order) for the plan's unchanged pattern."""
+    if int(vals.numel()) != plan.nnz:
+        raise ValueError("vals has the wrong length")
+    _check(_lib.spmm_plan_update_values(plan._h, _dev(vals, torch.float32) if plan.nnz else None,
+                                        _stream_ptr(stream)))
 
 
 def spmm_exec(plan: Plan, B, C_out=None, stream=None):

@@ -75,6 +75,7 @@ struct spmm_plan {
   int32_t* rowptr = nullptr;
   int32_t* colind = nullptr;
   float* csr_vals = nullptr;
+  uint32_t* ent_pos = nullptr;    // packed position of each CSR entry (value-only updates)
   // host copies used by the work-list builder and the synergy model
   std::vector<uint32_t> h_panel_ptr;
   std::vector<uint32_t> h_panel_nnzptr;   // first CSR entry of each panel
@@ -90,7 +91,7 @@ struct spmm_plan {
     lists.clear();
   }
   // the arrays above are carved out of two device allocations
-  char* fixed_arena = nullptr;   // panel_ptr, rowptr, colind, csr_vals
+  char* fixed_arena = nullptr;   // panel_ptr, rowptr, colind, csr_vals, ent_pos
   char* brick_arena = nullptr;   // brick_cols, brick_mask, brick_valptr, vals
   ~spmm_plan() {
     drop_lists();
@@ -314,13 +315,14 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   first_list = scratch.take<uint32_t>(nnz);
   ent_rank = scratch.take<uint32_t>(nnz);
 
-  fixed.cap = need(P + 1, 4) + need(M + 1, 4) + need(nnz, 4) + need(nnz, 4);
+  fixed.cap = need(P + 1, 4) + need(M + 1, 4) + 3 * need(nnz, 4);
   HIP_TRY(hipMalloc((void**)&fixed.base, fixed.cap));
   pl->fixed_arena = fixed.base;
   pl->panel_ptr = fixed.take<uint32_t>(P + 1);
   pl->rowptr = fixed.take<int32_t>(M + 1);
   pl->colind = fixed.take<int32_t>(nnz);
   pl->csr_vals = fixed.take<float>(nnz);
+  pl->ent_pos = fixed.take<uint32_t>(nnz);
 
   // ---- validation (device), before anything trusts the indices.  The column check only
   // dereferences rowptr[0..M] and colind[0..nnz), so it is safe to run on an invalid rowptr.
@@ -391,7 +393,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   // ---- a4: value offsets and packed values
   HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
   HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
-                             pl->vals, s));
+                             pl->vals, pl->ent_pos, s));
 
   // ---- a5: per-panel classes and the synergy counts
   HIP_TRY(hipMemsetAsync(counters, 0, kNumCounters * sizeof(unsigned long long), s));
@@ -428,6 +430,16 @@ done:
   }
   *out = pl;
   return SPMM_OK;
+}
+
+int spmm_plan_update_values(spmm_plan_t* pl, const float* vals, void* stream_) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (pl->nnz > 0 && !vals) return fail(SPMM_EINVAL, "vals is NULL with nnz > 0");
+  int status = SPMM_OK;
+  HIP_TRY(launch_update_values(vals, pl->ent_pos, pl->nnz, pl->vals, pl->csr_vals,
+                               (hipStream_t)stream_));
+done:
+  return status;
 }
 
 int spmm_exec(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream_) {

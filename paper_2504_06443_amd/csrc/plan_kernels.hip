@@ -182,12 +182,26 @@ __global__ void k_pack_values(const float* __restrict__ vals,
                               const uint8_t* __restrict__ ent_bit,
                               const uint64_t* __restrict__ brick_mask,
                               const uint32_t* __restrict__ brick_valptr, int64_t nnz,
-                              float* __restrict__ packed) {
+                              float* __restrict__ packed, uint32_t* __restrict__ ent_pos) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= nnz) return;
   const uint32_t b = ent_brick[e];
   const uint64_t below = brick_mask[b] & ((1ull << ent_bit[e]) - 1ull);
-  packed[(int64_t)brick_valptr[b] + __popcll(below)] = vals[e];
+  const uint32_t pos = brick_valptr[b] + (uint32_t)__popcll(below);
+  packed[pos] = vals[e];
+  ent_pos[e] = pos;
+}
+
+// New values for an unchanged pattern: entry e of the CSR goes to the packed position
+// recorded when the plan was built, and into the plan's CSR copy.
+__global__ void k_update_values(const float* __restrict__ vals,
+                                const uint32_t* __restrict__ ent_pos, int64_t nnz,
+                                float* __restrict__ packed, float* __restrict__ csr_vals) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= nnz) return;
+  const float v = vals[e];
+  packed[ent_pos[e]] = v;
+  csr_vals[e] = v;
 }
 
 // a5: per-panel class (Table 1, integer compare) and class totals.
@@ -426,10 +440,18 @@ hipError_t launch_scatter_bits(const int32_t* colind, const uint32_t* ent_row, c
 
 hipError_t launch_pack_values(const float* vals, const uint32_t* ent_brick, const uint8_t* ent_bit,
                               const uint64_t* brick_mask, const uint32_t* brick_valptr,
-                              int64_t nnz, float* packed, hipStream_t s) {
+                              int64_t nnz, float* packed, uint32_t* ent_pos, hipStream_t s) {
   if (nnz == 0) return hipSuccess;
   hipLaunchKernelGGL(k_pack_values, dim3(grid_for(nnz)), dim3(kThreads), 0, s, vals, ent_brick,
-                     ent_bit, brick_mask, brick_valptr, nnz, packed);
+                     ent_bit, brick_mask, brick_valptr, nnz, packed, ent_pos);
+  return hipGetLastError();
+}
+
+hipError_t launch_update_values(const float* vals, const uint32_t* ent_pos, int64_t nnz,
+                                float* packed, float* csr_vals, hipStream_t s) {
+  if (nnz == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_update_values, dim3(grid_for(nnz)), dim3(kThreads), 0, s, vals, ent_pos,
+                     nnz, packed, csr_vals);
   return hipGetLastError();
 }
 

@@ -69,7 +69,9 @@ hipError_t launch_scatter_bits(const int32_t* colind, const uint32_t* ent_row, c
                                uint8_t* col_seen, hipStream_t s);
 hipError_t launch_pack_values(const float* vals, const uint32_t* ent_brick, const uint8_t* ent_bit,
                               const uint64_t* brick_mask, const uint32_t* brick_valptr,
-                              int64_t nnz, float* packed, hipStream_t s);
+                              int64_t nnz, float* packed, uint32_t* ent_pos, hipStream_t s);
+hipError_t launch_update_values(const float* vals, const uint32_t* ent_pos, int64_t nnz,
+                                float* packed, float* csr_vals, hipStream_t s);
 hipError_t launch_panel_classes(const uint32_t* panel_ptr, const uint32_t* panel_nnzptr, int64_t P,
                                 uint8_t* panel_class, unsigned long long* counters, hipStream_t s);
 hipError_t launch_brick_hist(const uint64_t* brick_mask, int64_t nb, unsigned long long* counters,

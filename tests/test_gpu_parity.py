@@ -323,3 +323,30 @@ def test_error_paths_on_device(gpu):
     # the plan is still usable
     gpu.spmm_exec(plan, B, C)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["uniform_ragged", "blocks", "powerlaw", "sweep_high", "empty",
+                                  "single"])
+def test_update_values_keeps_pattern_and_replaces_values(gpu, name):
+    """Value-only update (Section 6, pre-processing overheads: one pattern, many products):
+    afterwards the exported format equals the oracle's format of the new matrix bit for bit,
+    and every route multiplies with the new values."""
+    import torch
+    A = SMALL[name]()
+    plan = make_plan(gpu, A)
+    rng = np.random.default_rng(123)
+    new_vals = rng.uniform(-1, 1, A.nnz).astype(np.float32)
+    if A.nnz > 3:
+        new_vals[::3] = 0.0            # zeros stay stored entries
+    gpu.spmm_plan_update_values(plan, torch.from_numpy(new_vals).cuda())
+    torch.cuda.synchronize()
+    ref = oracle.build_bricks(A.M, A.rowptr, A.colind, new_vals)
+    assert_format_equal(gpu.spmm_plan_export(plan), ref)
+    N = 48
+    B = W.dense_b(A.K, N, 9)
+    Cref, S = oracle.spmm_f64(A.rowptr, A.colind, new_vals, B)
+    A2 = W.CSR(A.M, A.K, A.rowptr, A.colind, new_vals)
+    for route in (gpu.ROUTE_AUTO, gpu.ROUTE_CLASS, gpu.ROUTE_VALU):
+        check_c(run_product(gpu, plan, A2, B, route=route), Cref, S)
+    with pytest.raises(ValueError):
+        gpu.spmm_plan_update_values(plan, torch.zeros(A.nnz + 1, device="cuda"))
