@@ -246,9 +246,11 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma(
 //     the LDS port;
 //   * loads use a scalar base plus a 32-bit lane offset.
 // The arrays behind BrickFormat carry kFormatPad spare bricks at the end, so
-// metadata is fetched 8 bricks at a time without clamping, and the loads issued
-// for the few steps past a work item's last brick touch valid memory; their
-// data is never used.
+// patterns and value offsets are fetched 8 bricks at a time without clamping.
+// The loads issued for the few steps past a work item's last brick repeat that
+// brick's B rows and values (cache hits, data never used): with short panels (ten
+// bricks, say) four steps of the next panel's rows would otherwise add 40 % to
+// the traffic from memory.
 constexpr int kFastChunk = 8;
 
 template <int T>
@@ -311,7 +313,11 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     // lane 4*i + c: byte offset of B row brick_cols[4*(base+i) + c]; pad columns
     // (0xFFFFFFFF) clamp to the last row, which is harmless since A is 0 there
     auto load_rowoff = [&](uint32_t base) {
-      const uint32_t c = brick_cols[(int64_t)base * kBrickK + (lane & (CH * kBrickK - 1))];
+      // steps past the work item's last brick re-read that brick's rows (cache hits) instead
+      // of pulling the next panel's B rows through the memory system for nothing
+      const uint32_t slot = (uint32_t)lane & (CH * kBrickK - 1);
+      const uint32_t idx = min(base * kBrickK + slot, (b_end - 1) * kBrickK + (slot & (kBrickK - 1)));
+      const uint32_t c = brick_cols[idx];
       return min(c, k_last) * row_bytes;
     };
 
@@ -350,6 +356,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
 
     Meta cur = load_meta(b_begin);
     uint32_t ro_cur = load_rowoff(b_begin);
+    const uint32_t off_last = brick_valptr[b_end - 1];
     // keep the first fetch from being merged with the in-loop fetch into one
     // load at the top of the loop (which would expose its latency every chunk)
     asm volatile("" : "+v"(ro_cur));
@@ -376,7 +383,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
         const uint32_t ro = ro_next;
         ro_next = (i + 1 < CH) ? __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_cur)
                                : __builtin_amdgcn_ds_bpermute(perm_base, ro_nxt);
-        issue(cur.mask[i], cur.off[i], ro, i % R);
+        const bool live = g < nbricks;   // uniform: scalar selects
+        issue(live ? cur.mask[i] : 0ull, live ? cur.off[i] : off_last, ro, i % R);
       }
       cur = nxt;
       ro_cur = ro_nxt;
