@@ -281,8 +281,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
 
   const int j = lane & 15;
   const int kq = lane >> 4;
-  const int bit = 4 * j + kq;
-  const uint64_t below = (1ull << bit) - 1ull;
+  const uint32_t perm_transpose = 4u * (uint32_t)(4 * j + kq);  // ds_bpermute: read lane 4j + kq
   const int64_t ncol0 = (int64_t)blockIdx.y * (16 * T) + V * j;
   const uint32_t row_bytes = (uint32_t)N * 4u;
   // byte offset of this lane's vectors inside a B row (columns >= N: clamped, never stored)
@@ -324,16 +323,20 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     uint64_t st_mask[R];
     float st_a[R];
     float st_b[R][T];
-    // Each lane needs the packed value whose index is the number of pattern bits below its
-    // own bit (the prefix-count decode of Algorithm 1), or zero if its bit is clear.  Wide
-    // tiles fetch it with a per-lane gather in flight with the B rows.  For narrow tiles the
-    // vector-memory pipe is the bottleneck, and a gather costs it as much as a dwordx4 load:
-    // there the values are fetched coalesced (lane l reads value l; lanes past the brick's
-    // count read neighbouring, valid memory) and compute() picks across lanes.
-    constexpr bool kCoalescedValues = T <= 2;
+    // Decode (the prefix-count decode of Algorithm 1) in pattern-bit order, then transpose:
+    // lane l first acts for pattern bit l.  Its value index is the number of pattern bits
+    // below bit l, which is what v_mbcnt computes from the wave-uniform pattern in two
+    // instructions; the gather that fetches it has addresses that never decrease from lane
+    // to lane, which the vector-memory pipe handles as cheaply as a contiguous load (a gather
+    // in MFMA lane order costs it as much as a dwordx4 load).  Lanes whose bit is clear are
+    // zeroed with the pattern itself as the select mask.  One ds_bpermute (LDS port, no
+    // vector-ALU slot) then moves element (row r, column c) from lane 4r + c to the lane the
+    // MFMA wants it in, 16c + r.
     auto issue = [&](uint64_t mask, uint32_t off, uint32_t ro, int s) {
       st_mask[s] = mask;
-      st_a[s] = vals[(int64_t)off + (kCoalescedValues ? lane : __popcll(mask & below))];
+      const uint32_t cnt = __builtin_amdgcn_mbcnt_hi(
+          (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+      st_a[s] = vals[(int64_t)off + cnt];
 #pragma unroll
       for (int q = 0; q < NV; ++q) {
         float tmp[V];
@@ -343,12 +346,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
       }
     };
     auto compute = [&](int s) {
-      const uint64_t m = st_mask[s];
-      float got = st_a[s];
-      if constexpr (kCoalescedValues)
-        got = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                            4 * __popcll(m & below), __builtin_bit_cast(int, got)));
-      const float a = ((m >> bit) & 1ull) ? got : 0.f;
+      float in_bit_order;
+      asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(in_bit_order) : "v"(st_a[s]), "s"(st_mask[s]));
+      const float a = __builtin_bit_cast(
+          float, __builtin_amdgcn_ds_bpermute(perm_transpose, __builtin_bit_cast(int, in_bit_order)));
 #pragma unroll
       for (int u = 0; u < T; ++u)
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, st_b[s][u], acc[u], 0, 0, 0);
@@ -370,24 +371,36 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     // steps that hold no brick.
     const uint32_t total = nbricks + R;
     uint32_t ro_next = __builtin_amdgcn_ds_bpermute(perm_base, ro_cur);
-    for (uint32_t c = 0; c < total; c += CH) {
+    auto step = [&](int i, uint32_t g, const Meta& m, uint32_t ro_this, uint32_t ro_following) {
+      if (g >= (uint32_t)R && g - R < nbricks) compute(i % R);
+      // this lane's row offset was fetched across lanes one step ago (its LDS-port latency
+      // hides behind the MFMAs above); fetch the next brick's now
+      const uint32_t ro = ro_next;
+      ro_next = (i + 1 < CH) ? __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_this)
+                             : __builtin_amdgcn_ds_bpermute(perm_base, ro_following);
+      const bool live = g < nbricks;   // uniform: scalar selects
+      issue(live ? m.mask[i] : 0ull, live ? m.off[i] : off_last, ro, i % R);
+    };
+    // Whole chunks run in a loop whose only exit is at its top; the last, partial chunk is
+    // straight-line code after it.  With an exit in the middle of the loop body the compiler
+    // must assume, at the loop head, that the steps after that exit issued no loads (it
+    // cannot see that the loop ends on that path), and it then waits for all but the newest
+    // load at the start of every chunk, which empties the ring every CH bricks.
+    uint32_t c = 0;
+    for (; c + CH <= total; c += CH) {
       const Meta nxt = load_meta(b_begin + c + CH);
       const uint32_t ro_nxt = load_rowoff(b_begin + c + CH);
 #pragma unroll
-      for (int i = 0; i < CH; ++i) {
-        const uint32_t g = c + i;
-        if (i % R == 0 && i > 0 && g >= total) break;
-        if (g >= (uint32_t)R && g - R < nbricks) compute(i % R);
-        // this lane's row offset was fetched across lanes one step ago (its LDS-port latency
-        // hides behind the MFMAs above); fetch the next brick's now
-        const uint32_t ro = ro_next;
-        ro_next = (i + 1 < CH) ? __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_cur)
-                               : __builtin_amdgcn_ds_bpermute(perm_base, ro_nxt);
-        const bool live = g < nbricks;   // uniform: scalar selects
-        issue(live ? cur.mask[i] : 0ull, live ? cur.off[i] : off_last, ro, i % R);
-      }
+      for (int i = 0; i < CH; ++i) step(i, c + i, cur, ro_cur, ro_nxt);
       cur = nxt;
       ro_cur = ro_nxt;
+    }
+    if (c < total) {
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        if (i % R == 0 && i > 0 && c + i >= total) break;
+        step(i, c + i, cur, ro_cur, ro_cur);
+      }
     }
   }
 
