@@ -279,41 +279,63 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   const int64_t P = (M + kPanel - 1) / kPanel;
   pl->M = M; pl->K = K; pl->nnz = nnz; pl->P = P;
 
-  // Device memory comes from three allocations: scratch (freed before returning), the plan's
-  // fixed-size arrays, and the brick arrays once their count is known.  Sub-arrays are
-  // 256-byte aligned.
+  // Device memory comes from three allocations (four on the search-based path): scratch
+  // (freed before returning), the plan's fixed-size arrays, and the brick arrays once their
+  // count is known.  Sub-arrays are 256-byte aligned.
   auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
-  Arena scratch, fixed, bricks;
-  uint32_t *d_err, *ent_row, *first_scan, *scan_tmp, *nbricks_p, *panel_nnzptr, *ent_brick;
-  uint32_t *link, *first_list, *ent_rank;
-  uint8_t *first, *ent_bit, *col_seen, *panel_class;
-  unsigned long long* counters;
-  uint32_t h_err = 0, h_nb = 0, h_active = 0;
+  Arena scratch, wide, fixed, bricks;
+  uint32_t *d_err, *d_span, *d_maxnb, *scan_tmp, *nbricks_p, *panel_nnzptr;
+  bool per_panel = false;
+  uint32_t h_maxnb = 0;
+  uint8_t *col_seen, *panel_class;
+  unsigned long long *counters, *d_active;
+  uint32_t h_small[2] = {0, 0};   // error bits, widest panel span
+  uint32_t h_err = 0, h_nb = 0, words_cap = 0;
+  unsigned long long h_active = 0;
   const int64_t scan_elems = (int64_t)scan_tmp_elems(std::max(nnz, P + 1));  // bricks <= nnz
+
+  // a1 of the search-based path: row of every entry (with the column check), first occurrences,
+  // their scan and compacted list, bricks per panel
+  auto wide_a1 = [&]() -> int {
+    int status = SPMM_OK;
+    uint32_t *ent_row, *first_scan, *link, *first_list;
+    uint8_t* first;
+    wide.cap = need(nnz, 4) + need(nnz, 1) + need(nnz + 1, 4) + need(nnz, 4) + need(nnz, 1) +
+               3 * need(nnz, 4);
+    HIP_TRY(hipMalloc((void**)&wide.base, wide.cap));
+    ent_row = wide.take<uint32_t>(nnz);
+    first = wide.take<uint8_t>(nnz);
+    first_scan = wide.take<uint32_t>(nnz + 1);
+    link = wide.take<uint32_t>(nnz);
+    first_list = wide.take<uint32_t>(nnz);
+    HIP_TRY(launch_validate_cols(rowptr, colind, M, K, nnz, ent_row, d_err, s));
+    HIP_TRY(launch_first_in_panel(rowptr, colind, ent_row, nnz, first, link, s));
+    HIP_TRY(launch_scan_u8(first, nnz, first_scan, scan_tmp, s));
+    HIP_TRY(launch_compact_first(first, first_scan, nnz, first_list, s));
+    HIP_TRY(launch_panel_counts(rowptr, first_scan, M, P, nbricks_p, panel_nnzptr, s));
+    HIP_TRY(hipMemsetAsync(d_active, 0, sizeof(unsigned long long), s));
+    HIP_TRY(hipMemcpyAsync(d_active, first_scan + nnz, sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+  done:
+    return status;
+  };
 
   HIP_TRY(hipGetDevice(&pl->device));
   HIP_TRY(hipDeviceGetAttribute(&pl->num_cus, hipDeviceAttributeMultiprocessorCount, pl->device));
   pl->num_cus = std::max(1, pl->num_cus);
 
-  scratch.cap = need(1, 4) + need(nnz, 4) + need(nnz, 1) + need(nnz + 1, 4) + need(scan_elems, 4) +
-                need(P, 4) + need(P + 1, 4) + need(nnz, 4) + need(nnz, 1) + need(K, 1) + need(P, 1) +
-                need(kNumCounters, 8) + 3 * need(nnz, 4);
+  scratch.cap = need(3, 4) + need(scan_elems, 4) + need(P, 4) + need(P + 1, 4) + need(K, 1) +
+                need(P, 1) + need(kNumCounters, 8) + need(1, 8);
   HIP_TRY(hipMalloc((void**)&scratch.base, scratch.cap));
-  d_err = scratch.take<uint32_t>(1);
-  ent_row = scratch.take<uint32_t>(nnz);
-  first = scratch.take<uint8_t>(nnz);
-  first_scan = scratch.take<uint32_t>(nnz + 1);
+  d_err = scratch.take<uint32_t>(3);
+  d_span = d_err + 1;
+  d_maxnb = d_err + 2;
   scan_tmp = scratch.take<uint32_t>(scan_elems);
   nbricks_p = scratch.take<uint32_t>(P);
   panel_nnzptr = scratch.take<uint32_t>(P + 1);
-  ent_brick = scratch.take<uint32_t>(nnz);
-  ent_bit = scratch.take<uint8_t>(nnz);
   col_seen = scratch.take<uint8_t>(K);
   panel_class = scratch.take<uint8_t>(P);
   counters = scratch.take<unsigned long long>(kNumCounters);
-  link = scratch.take<uint32_t>(nnz);
-  first_list = scratch.take<uint32_t>(nnz);
-  ent_rank = scratch.take<uint32_t>(nnz);
+  d_active = scratch.take<unsigned long long>(1);
 
   fixed.cap = need(P + 1, 4) + need(M + 1, 4) + 3 * need(nnz, 4);
   HIP_TRY(hipMalloc((void**)&fixed.base, fixed.cap));
@@ -324,35 +346,45 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   pl->csr_vals = fixed.take<float>(nnz);
   pl->ent_pos = fixed.take<uint32_t>(nnz);
 
-  // ---- validation (device), before anything trusts the indices.  The column check only
-  // dereferences rowptr[0..M] and colind[0..nnz), so it is safe to run on an invalid rowptr.
-  HIP_TRY(hipMemsetAsync(d_err, 0, sizeof(uint32_t), s));
+  // ---- rowptr validation and the widest panel span (device), before anything trusts rowptr
+  HIP_TRY(hipMemsetAsync(d_err, 0, 2 * sizeof(uint32_t), s));
+  HIP_TRY(hipMemsetAsync(d_active, 0, sizeof(unsigned long long), s));
   HIP_TRY(launch_validate_rowptr(rowptr, M, nnz, d_err, s));
-  HIP_TRY(launch_validate_cols(rowptr, colind, M, K, nnz, ent_row, d_err, s));
-  HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(launch_panel_span(rowptr, colind, M, P, d_err, d_span, s));
+  HIP_TRY(hipMemcpyAsync(h_small, d_err, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  h_err = h_small[0];
   if (h_err & (kErrRowptrEnds | kErrRowptrOrder)) {
     status = fail(SPMM_EFORMAT, "invalid rowptr (%s)",
                   (h_err & kErrRowptrEnds) ? "rowptr[0] != 0 or rowptr[M] != nnz" : "not monotone");
     goto done;
   }
-  if (h_err) {
-    status = fail(SPMM_EFORMAT, "invalid colind (%s)",
-                  (h_err & kErrColRange) ? "column out of range"
-                                         : "columns of a row not strictly ascending");
-    goto done;
+  words_cap = panel_bitmap_words(h_small[1]);
+
+  // The per-panel kernels walk a bitmap over the panel's column span; that pays while the
+  // bitmaps are not much longer than the entry lists (band-like matrices).  Scattered
+  // matrices (power-law graphs, random bricks: spans near K) take the search-based kernels.
+  // Measured: config 5 (bitmap words x panels = 4 x nnz) 0.6 vs 1.0 ms in favour of the
+  // bitmap, config 3 (360 x) 4.0 vs 0.9 ms and the 1M-row sweep (67 x) 31 vs 3.8 ms against it.
+  per_panel = words_cap != 0 && (int64_t)words_cap * P <= 8 * nnz;
+  if (per_panel) {
+    // ---- per-panel path, a1/a2: census (also validates colind) -> bricks per panel
+    HIP_TRY(hipMemsetAsync(d_maxnb, 0, sizeof(uint32_t), s));
+    HIP_TRY(launch_panel_census(rowptr, colind, M, K, P, words_cap, d_err, nbricks_p, panel_nnzptr,
+                                d_active, d_maxnb, s));
+  } else {
+    // ---- search-based path for matrices with a panel wider than the LDS bitmap.  Its a1
+    // kernels only compare columns, so they may run before the host has seen the verdict of
+    // the column check; everything that indexes by column or rank runs after it.
+    status = wide_a1();
+    if (status != SPMM_OK) goto done;
   }
-
-  // ---- a1: first occurrence of each column in its panel, scanned
-  HIP_TRY(launch_first_in_panel(rowptr, colind, ent_row, nnz, first, link, s));
-  HIP_TRY(launch_scan_u8(first, nnz, first_scan, scan_tmp, s));
-  HIP_TRY(launch_compact_first(first, first_scan, nnz, first_list, s));
-
-  // ---- a2: bricks per panel -> panel_ptr
-  HIP_TRY(launch_panel_counts(rowptr, first_scan, M, P, nbricks_p, panel_nnzptr, s));
   HIP_TRY(launch_scan_u32(nbricks_p, P, pl->panel_ptr, scan_tmp, s));
   HIP_TRY(hipMemcpyAsync(&h_nb, pl->panel_ptr + P, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipMemcpyAsync(&h_active, first_scan + nnz, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(&h_active, d_active, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  if (per_panel)
+    HIP_TRY(hipMemcpyAsync(&h_maxnb, d_maxnb, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   // plan-owned CSR copy for the vector-ALU kernel, while the host waits for the counts
   HIP_TRY(hipMemcpyAsync(pl->rowptr, rowptr, (size_t)(M + 1) * sizeof(int32_t),
                          hipMemcpyDeviceToDevice, s));
@@ -363,14 +395,26 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
                            hipMemcpyDeviceToDevice, s));
   }
   HIP_TRY(hipStreamSynchronize(s));
+  if (h_err) {
+    status = fail(SPMM_EFORMAT, "invalid colind (%s)",
+                  (h_err & kErrColRange) ? "column out of range"
+                                         : "columns of a row not strictly ascending");
+    goto done;
+  }
   pl->nb = h_nb;
-  pl->n_active_cols = h_active;
+  pl->n_active_cols = (int64_t)h_active;
   if ((int64_t)h_nb * kBrickK >= (int64_t(1) << 32)) {
     status = fail(SPMM_ELIMIT, "4 * bricks must be below 2^32");
     goto done;
   }
 
-  // ---- a2/a3: brick columns and patterns (arrays carry spare entries, see BrickFormat)
+  if (per_panel && !panel_build_fits(words_cap, std::max<uint32_t>(h_maxnb, 1))) {
+    per_panel = false;   // a panel with more bricks than fit in LDS: finish on the search-based path
+    status = wide_a1();
+    if (status != SPMM_OK) goto done;
+  }
+
+  // ---- brick arrays (they carry spare entries, see BrickFormat)
   bricks.cap = need((pl->nb + kFormatPad) * kBrickK, 4) + need(pl->nb + kFormatPad, 8) +
                need(pl->nb + 1 + kFormatPad, 4) + need(nnz + 64, 4);
   HIP_TRY(hipMalloc((void**)&bricks.base, bricks.cap));
@@ -379,26 +423,42 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   pl->brick_mask = bricks.take<uint64_t>(pl->nb + kFormatPad);
   pl->brick_valptr = bricks.take<uint32_t>(pl->nb + 1 + kFormatPad);
   pl->vals = bricks.take<float>(nnz + 64);
-  HIP_TRY(launch_fill_u32(pl->brick_cols, pl->nb * kBrickK, kPadCol, s));
   HIP_TRY(hipMemsetAsync(pl->brick_cols + pl->nb * kBrickK, 0, kFormatPad * kBrickK * 4, s));
   HIP_TRY(hipMemsetAsync(pl->brick_mask, 0, (size_t)(pl->nb + kFormatPad) * 8, s));
-  HIP_TRY(launch_fill_u32(pl->brick_valptr + pl->nb + 1, kFormatPad, (uint32_t)nnz, s));
+  HIP_TRY(launch_fill_u32(pl->brick_valptr + pl->nb, kFormatPad + 1, (uint32_t)nnz, s));
   HIP_TRY(hipMemsetAsync(pl->vals + nnz, 0, 64 * sizeof(float), s));
   HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
-  HIP_TRY(launch_rank_first(rowptr, colind, ent_row, first_list, first_scan, pl->panel_ptr, M,
-                            pl->n_active_cols, ent_rank, pl->brick_cols, s));
-  HIP_TRY(launch_scatter_bits(colind, ent_row, link, ent_rank, pl->panel_ptr, nnz, pl->brick_mask,
-                              ent_brick, ent_bit, col_seen, s));
-
-  // ---- a4: value offsets and packed values
-  HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
-  HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
-                             pl->vals, pl->ent_pos, s));
-
-  // ---- a5: per-panel classes and the synergy counts
   HIP_TRY(hipMemsetAsync(counters, 0, kNumCounters * sizeof(unsigned long long), s));
-  HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
-  HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
+
+  if (per_panel) {
+    // ---- a2 (placing), a3, a4 and the per-panel part of a5, one wavefront per panel
+    HIP_TRY(launch_panel_build(rowptr, colind, vals, M, K, P, words_cap,
+                               std::max<uint32_t>(h_maxnb, 1), pl->panel_ptr,
+                               pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals,
+                               pl->ent_pos, col_seen, panel_class, counters, s));
+  } else {
+    // the arrays of the search-based path, in the order they were carved above
+    Arena again = wide;
+    again.used = 0;
+    uint32_t* ent_row = again.take<uint32_t>(nnz);
+    (void)again.take<uint8_t>(nnz);
+    uint32_t* first_scan = again.take<uint32_t>(nnz + 1);
+    uint32_t* link = again.take<uint32_t>(nnz);
+    uint32_t* first_list = again.take<uint32_t>(nnz);
+    uint32_t* ent_brick = again.take<uint32_t>(nnz);
+    uint8_t* ent_bit = again.take<uint8_t>(nnz);
+    uint32_t* ent_rank = again.take<uint32_t>(nnz);
+    HIP_TRY(launch_fill_u32(pl->brick_cols, pl->nb * kBrickK, kPadCol, s));
+    HIP_TRY(launch_rank_first(rowptr, colind, ent_row, first_list, first_scan, pl->panel_ptr, M,
+                              pl->n_active_cols, ent_rank, pl->brick_cols, s));
+    HIP_TRY(launch_scatter_bits(colind, ent_row, link, ent_rank, pl->panel_ptr, nnz,
+                                pl->brick_mask, ent_brick, ent_bit, col_seen, s));
+    HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
+    HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
+                               pl->vals, pl->ent_pos, s));
+    HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
+    HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
+  }
   HIP_TRY(launch_count_flags(col_seen, K, counters + kCntDistinctCols, s));
 
   // ---- host copies for the work-list builder and the model
@@ -424,6 +484,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
 done:
   if (status != SPMM_OK) (void)hipStreamSynchronize(s);
   if (scratch.base) (void)hipFree(scratch.base);
+  if (wide.base) (void)hipFree(wide.base);
   if (status != SPMM_OK) {
     delete pl;
     return status;

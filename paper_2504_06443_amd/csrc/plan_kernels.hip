@@ -350,6 +350,270 @@ hipError_t scan_impl(Load load, int64_t n, uint32_t* out, uint32_t* tmp, hipStre
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- per-panel path
+// One wavefront (a 64-thread workgroup) per panel, the panel's active columns as a bitmap in
+// LDS over the panel's column span [cmin, cmax]: setting a bit per entry is the census (a1),
+// the number of set bits below a column is its rank (a2), and from the rank follow brick,
+// brick column and pattern bit (a3, patterns accumulated in LDS) and, after a scan of the
+// panel's pattern popcounts, the value positions (a4; a panel's values are contiguous, so
+// brick_valptr needs no scan across panels).  Used when the widest panel span and the largest
+// brick count of a panel fit in LDS; other matrices take the search-based kernels above.
+constexpr int kPanelThreads = 64;
+constexpr int kGroupWords = 8;   // bitmap words per entry of the coarse rank table
+constexpr uint32_t kPanelMaxWords = 32768;          // 1 Mi columns of span
+constexpr size_t kPanelMaxLds = 150 * 1024;         // of the 160 KiB of a CU
+
+struct PanelExtent {
+  int64_t e0, e1;        // entries of the panel
+  int32_t cmin, cmax;    // column span (valid if e0 < e1)
+};
+
+// exclusive scan of one value per lane across the wavefront; returns the total in *total_out
+__device__ inline uint32_t wave_exclusive(uint32_t v, uint32_t* total_out) {
+  const int lane = threadIdx.x & 63;
+  uint32_t incl = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += up;
+  }
+  *total_out = __shfl(incl, 63, 64);
+  return incl - v;
+}
+
+// rows of panel p -> rp[0..16] (entry offsets, repeated past the last row), span of columns
+__device__ inline PanelExtent panel_extent(const int32_t* __restrict__ rowptr,
+                                           const int32_t* __restrict__ colind, int64_t M,
+                                           int64_t p, int32_t* rp /* LDS [17] */) {
+  const int64_t r0 = p * kPanel;
+  if (threadIdx.x <= kPanel) rp[threadIdx.x] = rowptr[min(r0 + (int64_t)threadIdx.x, M)];
+  __syncthreads();
+  int32_t lo = 0x7FFFFFFF, hi = -1;
+  if (threadIdx.x < kPanel) {
+    const int32_t s = rp[threadIdx.x], t = rp[threadIdx.x + 1];
+    if (s < t) {   // sorted rows: first and last entry bound the row's columns
+      lo = colind[s];
+      hi = colind[t - 1];
+    }
+  }
+#pragma unroll
+  for (int d = 8; d > 0; d >>= 1) {   // rows sit in lanes 0..15
+    lo = min(lo, __shfl_xor(lo, d, 64));
+    hi = max(hi, __shfl_xor(hi, d, 64));
+  }
+  lo = __shfl(lo, 0, 64);
+  hi = __shfl(hi, 0, 64);
+  return PanelExtent{rp[0], rp[kPanel], lo, hi};
+}
+
+// row (0..15) of entry e inside the panel whose row offsets are rp[0..16]
+__device__ inline int row_in_panel(const int32_t* rp, int64_t e) {
+  int r = 0;
+#pragma unroll
+  for (int d = 8; d > 0; d >>= 1)
+    if (rp[r + d] <= e) r += d;
+  return r;
+}
+
+// widest column span of any panel (0 for an empty matrix); requires a valid rowptr
+__global__ void k_panel_span(const int32_t* __restrict__ rowptr,
+                             const int32_t* __restrict__ colind, int64_t M, int64_t P,
+                             const uint32_t* __restrict__ err, uint32_t* max_span) {
+  if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= P) return;
+  int32_t lo = 0x7FFFFFFF, hi = -1;
+  for (int64_t r = p * kPanel; r < min((p + 1) * kPanel, M); ++r) {
+    const int32_t s = rowptr[r], t = rowptr[r + 1];
+    if (s < t) { lo = min(lo, colind[s]); hi = max(hi, colind[t - 1]); }
+  }
+  if (hi >= lo) atomicMax(max_span, (uint32_t)((int64_t)hi - lo + 1));
+}
+
+// sets the panel's bitmap; checks the columns on the way (range, order, inside the span)
+__device__ inline void panel_bitmap(const int32_t* __restrict__ colind, const PanelExtent& x,
+                                    const int32_t* rp, int64_t K, uint32_t words, uint32_t* bm,
+                                    uint32_t* err) {
+  for (uint32_t w = threadIdx.x; w < words; w += kPanelThreads) bm[w] = 0;
+  __syncthreads();
+  uint32_t bad = 0;
+  for (int64_t e = x.e0 + threadIdx.x; e < x.e1; e += kPanelThreads) {
+    const int32_t j = colind[e];
+    if (err) {
+      if (j < 0 || j >= K) bad |= kErrColRange;
+      if (e > rp[row_in_panel(rp, e)] && colind[e - 1] >= j) bad |= kErrColOrder;
+    }
+    if (j >= x.cmin && j <= x.cmax) {
+      const uint32_t d = (uint32_t)(j - x.cmin);
+      atomicOr(&bm[d >> 5], 1u << (d & 31));
+    } else {
+      bad |= kErrColOrder;   // outside the span its sorted row promised
+    }
+  }
+  if (err && bad) atomicOr(err, bad);
+  __syncthreads();
+}
+
+// a1/a2 (counting half): bricks of each panel, entry offset of each panel, total of active
+// columns, largest brick count of a panel; validates colind.  Dynamic LDS: the bitmap.
+__global__ __launch_bounds__(kPanelThreads) void k_panel_census(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind, int64_t M, int64_t K,
+    int64_t P, uint32_t words_cap, uint32_t* err, uint32_t* __restrict__ nbricks_p,
+    uint32_t* __restrict__ panel_nnzptr, unsigned long long* n_active, uint32_t* max_nb) {
+  extern __shared__ uint32_t lds[];
+  __shared__ int32_t rp[kPanel + 1];
+  if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;   // uniform: nothing below is safe
+  const int64_t p = blockIdx.x;
+  const PanelExtent x = panel_extent(rowptr, colind, M, p, rp);
+  if (threadIdx.x == 0) {
+    panel_nnzptr[p] = (uint32_t)x.e0;
+    if (p == P - 1) panel_nnzptr[P] = (uint32_t)x.e1;
+  }
+  if (x.e0 >= x.e1 || x.cmax < x.cmin) {
+    if (threadIdx.x == 0) nbricks_p[p] = 0;
+    return;
+  }
+  const uint32_t words = (uint32_t)(x.cmax - x.cmin) / 32u + 1u;
+  if (words > words_cap) {   // cannot happen for sorted rows (the cap comes from k_panel_span)
+    if (threadIdx.x == 0) { atomicOr(err, (uint32_t)kErrColOrder); nbricks_p[p] = 0; }
+    return;
+  }
+  panel_bitmap(colind, x, rp, K, words, lds, err);
+  uint32_t cnt = 0;
+  for (uint32_t w = threadIdx.x; w < words; w += kPanelThreads) cnt += __popc(lds[w]);
+  uint32_t total;
+  wave_exclusive(cnt, &total);
+  if (threadIdx.x == 0) {
+    const uint32_t nb = (total + kBrickK - 1) / kBrickK;
+    nbricks_p[p] = nb;
+    atomicAdd(n_active, (unsigned long long)total);
+    atomicMax(max_nb, nb);
+  }
+}
+
+// a2 (placing half), a3, a4 and the a5 counts for one panel.  Dynamic LDS: patterns of the
+// panel's bricks (nb_cap x u64), the bitmap (words_cap words), the coarse rank table
+// (words_cap / 8 + 1 words), value offsets of the panel's bricks (nb_cap words).
+__global__ __launch_bounds__(kPanelThreads) void k_panel_build(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
+    const float* __restrict__ vals, int64_t M, int64_t K, uint32_t words_cap, uint32_t nb_cap,
+    const uint32_t* __restrict__ panel_ptr, uint32_t* __restrict__ brick_cols,
+    uint64_t* __restrict__ brick_mask, uint32_t* __restrict__ brick_valptr,
+    float* __restrict__ packed, uint32_t* __restrict__ ent_pos, uint8_t* __restrict__ col_seen,
+    uint8_t* __restrict__ panel_class, unsigned long long* counters) {
+  extern __shared__ unsigned long long lds64[];
+  __shared__ int32_t rp[kPanel + 1];
+  __shared__ uint32_t hist[65];
+  unsigned long long* pat = lds64;                                   // [nb_cap]
+  uint32_t* bm = reinterpret_cast<uint32_t*>(lds64 + nb_cap);        // [words_cap]
+  uint32_t* pre = bm + words_cap;     // [words_cap / 8 + 1]; pre[g] = set bits in words [0, 8g)
+  uint32_t* vptr = pre + words_cap / kGroupWords + 1;                // [nb_cap]
+  const int64_t p = blockIdx.x;
+  const uint32_t pp = panel_ptr[p];
+  const uint32_t nb = panel_ptr[p + 1] - pp;
+  const PanelExtent x = panel_extent(rowptr, colind, M, p, rp);
+  if (nb == 0) {
+    if (threadIdx.x == 0) panel_class[p] = 255;
+    return;
+  }
+  const uint32_t words = (uint32_t)(x.cmax - x.cmin) / 32u + 1u;
+  for (uint32_t k = threadIdx.x; k < nb; k += kPanelThreads) pat[k] = 0;
+  for (uint32_t t = threadIdx.x; t < 65; t += kPanelThreads) hist[t] = 0;
+  panel_bitmap(colind, x, rp, K, words, bm, nullptr);
+
+  // coarse rank table: exclusive scan over groups of 8 words, a contiguous run per lane
+  const uint32_t ngroups = (words + kGroupWords - 1) / kGroupWords;
+  const uint32_t per = (ngroups + kPanelThreads - 1) / kPanelThreads;
+  const uint32_t g0 = min(threadIdx.x * per, ngroups), g1 = min(g0 + per, ngroups);
+  uint32_t mine = 0;
+  for (uint32_t g = g0; g < g1; ++g) {
+    uint32_t s = 0;
+    for (uint32_t w = g * kGroupWords; w < min((g + 1) * kGroupWords, words); ++w) s += __popc(bm[w]);
+    pre[g] = s;
+    mine += s;
+  }
+  uint32_t ncols;
+  uint32_t run = wave_exclusive(mine, &ncols);
+  for (uint32_t g = g0; g < g1; ++g) {
+    const uint32_t s = pre[g];
+    pre[g] = run;
+    run += s;
+  }
+  __syncthreads();
+  auto bits_before_word = [&](uint32_t w) {
+    uint32_t r = pre[w / kGroupWords];
+    for (uint32_t v = w & ~(uint32_t)(kGroupWords - 1); v < w; ++v) r += __popc(bm[v]);
+    return r;
+  };
+
+  // a2: active columns in ascending order, four per brick, the tail padded
+  for (uint32_t w = threadIdx.x; w < words; w += kPanelThreads) {
+    uint32_t bits = bm[w];
+    if (!bits) continue;
+    uint32_t r = bits_before_word(w);
+    while (bits) {
+      const uint32_t col = (uint32_t)x.cmin + 32u * w + (uint32_t)__builtin_ctz(bits);
+      brick_cols[(int64_t)pp * kBrickK + r++] = col;
+      col_seen[col] = 1;
+      bits &= bits - 1;
+    }
+  }
+  for (uint32_t k = ncols + threadIdx.x; k < nb * kBrickK; k += kPanelThreads)
+    brick_cols[(int64_t)pp * kBrickK + k] = kPadCol;
+
+  // a3: pattern bits, accumulated in LDS
+  for (int64_t e = x.e0 + threadIdx.x; e < x.e1; e += kPanelThreads) {
+    const uint32_t d = (uint32_t)(colind[e] - x.cmin);
+    const uint32_t rank = bits_before_word(d >> 5) + __popc(bm[d >> 5] & ((1u << (d & 31)) - 1u));
+    const uint32_t bit = (uint32_t)row_in_panel(rp, e) * kBrickK + rank % kBrickK;
+    atomicOr(&pat[rank / kBrickK], 1ull << bit);
+  }
+  __syncthreads();
+
+  // a4: value offsets = entries before the panel + popcounts of the panel's earlier bricks
+  uint32_t carry = (uint32_t)x.e0;
+  for (uint32_t base = 0; base < nb; base += kPanelThreads) {
+    const uint32_t k = base + threadIdx.x;
+    uint32_t c = 0;
+    if (k < nb) {
+      const unsigned long long m = pat[k];
+      brick_mask[pp + k] = m;
+      c = (uint32_t)__popcll(m);
+      atomicAdd(&hist[c], 1u);
+    }
+    uint32_t total;
+    const uint32_t ex = wave_exclusive(c, &total);
+    if (k < nb) {
+      vptr[k] = carry + ex;
+      brick_valptr[pp + k] = carry + ex;
+    }
+    carry += total;
+  }
+  __syncthreads();
+  for (int64_t e = x.e0 + threadIdx.x; e < x.e1; e += kPanelThreads) {
+    const uint32_t d = (uint32_t)(colind[e] - x.cmin);
+    const uint32_t rank = bits_before_word(d >> 5) + __popc(bm[d >> 5] & ((1u << (d & 31)) - 1u));
+    const uint32_t bit = (uint32_t)row_in_panel(rp, e) * kBrickK + rank % kBrickK;
+    const uint32_t k = rank / kBrickK;
+    const uint32_t pos = vptr[k] + (uint32_t)__popcll(pat[k] & ((1ull << bit) - 1ull));
+    packed[pos] = vals[e];
+    ent_pos[e] = pos;
+  }
+
+  // a5: class of the panel (Table 1, integer compare), class totals, popcount histogram
+  if (threadIdx.x == 0) {
+    const unsigned long long nz = (unsigned long long)(x.e1 - x.e0);
+    const uint8_t cls = nz < 8ull * nb ? 0 : (nz < 16ull * nb ? 1 : 2);
+    panel_class[p] = cls;
+    atomicAdd(&counters[kCntPanelsByClass + cls], 1ull);
+    atomicAdd(&counters[kCntBricksByClass + cls], (unsigned long long)nb);
+    atomicAdd(&counters[kCntNnzByClass + cls], nz);
+    atomicAdd(&counters[kCntNonEmptyPanels], 1ull);
+  }
+  for (uint32_t t = threadIdx.x; t < 65; t += kPanelThreads)
+    if (hist[t]) atomicAdd(&counters[kCntPopHist + t], (unsigned long long)hist[t]);
+}
+
 }  // namespace
 
 size_t scan_tmp_elems(int64_t n) { return (size_t)((n + kScanTile - 1) / kScanTile) + 1; }
@@ -476,6 +740,66 @@ hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long lon
   if (n == 0) return hipSuccess;
   const unsigned g = (unsigned)std::min<int64_t>(grid_for(n), 2048);
   hipLaunchKernelGGL(k_count_flags, dim3(g), dim3(kThreads), 0, s, flags, n, counter);
+  return hipGetLastError();
+}
+
+// ---- per-panel path
+hipError_t launch_panel_span(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t P,
+                             const uint32_t* err, uint32_t* max_span, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_panel_span, dim3(grid_for(P)), dim3(kThreads), 0, s, rowptr, colind, M, P,
+                     err, max_span);
+  return hipGetLastError();
+}
+
+// bitmap words (a power of two, at least 64) for a widest panel span of `span` columns, or 0 if
+// that does not fit the LDS bitmap
+uint32_t panel_bitmap_words(uint32_t span) {
+  uint32_t words = 64;
+  while ((uint64_t)words * 32 < span && words < kPanelMaxWords) words *= 2;
+  return (uint64_t)words * 32 >= span ? words : 0;
+}
+
+// LDS bytes of k_panel_build for a bitmap of words_cap words and panels of up to nb_cap bricks
+static size_t panel_build_lds(uint32_t words_cap, uint32_t nb_cap) {
+  return (size_t)nb_cap * 8 + ((size_t)words_cap + words_cap / kGroupWords + 1 + nb_cap) * 4;
+}
+bool panel_build_fits(uint32_t words_cap, uint32_t nb_cap) {
+  return words_cap != 0 && panel_build_lds(words_cap, nb_cap) <= kPanelMaxLds;
+}
+
+hipError_t launch_panel_census(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t K,
+                               int64_t P, uint32_t words_cap, uint32_t* err, uint32_t* nbricks_p,
+                               uint32_t* panel_nnzptr, unsigned long long* n_active,
+                               uint32_t* max_nb, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t lds = (size_t)words_cap * 4;
+  if (lds > 48 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_panel_census),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_panel_census, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr, colind,
+                     M, K, P, words_cap, err, nbricks_p, panel_nnzptr, n_active, max_nb);
+  return hipGetLastError();
+}
+
+hipError_t launch_panel_build(const int32_t* rowptr, const int32_t* colind, const float* vals,
+                              int64_t M, int64_t K, int64_t P, uint32_t words_cap, uint32_t nb_cap,
+                              const uint32_t* panel_ptr, uint32_t* brick_cols, uint64_t* brick_mask,
+                              uint32_t* brick_valptr, float* packed, uint32_t* ent_pos,
+                              uint8_t* col_seen, uint8_t* panel_class, unsigned long long* counters,
+                              hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t lds = panel_build_lds(words_cap, nb_cap);
+  if (lds > 48 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_panel_build),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_panel_build, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr, colind,
+                     vals, M, K, words_cap, nb_cap, panel_ptr, brick_cols, brick_mask, brick_valptr,
+                     packed, ent_pos, col_seen, panel_class, counters);
   return hipGetLastError();
 }
 

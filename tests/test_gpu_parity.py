@@ -350,3 +350,44 @@ def test_update_values_keeps_pattern_and_replaces_values(gpu, name):
         check_c(run_product(gpu, plan, A2, B, route=route), Cref, S)
     with pytest.raises(ValueError):
         gpu.spmm_plan_update_values(plan, torch.zeros(A.nnz + 1, device="cuda"))
+
+
+def test_plan_paths_for_wide_panels(gpu):
+    """The plan has a per-panel path (bitmap of the panel's column span in LDS) and a
+    search-based one.  Cases: a span beyond the largest bitmap (search-based); a scattered
+    matrix whose bitmaps would dwarf its entry lists (search-based by the cost rule); one panel
+    with a 700k-column span and many entries (per-panel, LDS allocation above the default
+    limit); the same with more bricks than LDS holds beside that bitmap (starts per-panel,
+    finishes search-based).  All must give the oracle's format, counts and product."""
+    rng = np.random.default_rng(77)
+
+    def scattered(K, M, n):
+        rows = rng.integers(0, M, n)
+        cols = np.concatenate([rng.integers(0, 50, n // 3), rng.integers(K - 50, K, n // 3),
+                               rng.integers(0, K, n - 2 * (n // 3))])
+        return W.csr_from_coo(M, K, rows, cols, rng.uniform(-1, 1, n).astype(np.float32))
+
+    def shared_columns(K, ncols):   # one panel, every row stores the same ncols columns
+        cols = np.sort(rng.choice(K, size=ncols, replace=False))
+        cols[0], cols[-1] = 0, K - 1
+        rows = np.repeat(np.arange(16), ncols)
+        return W.csr_from_coo(16, K, rows, np.tile(cols, 16),
+                              rng.uniform(-1, 1, 16 * ncols).astype(np.float32))
+
+    cases = {"beyond_bitmap": scattered(1_300_000, 70, 900),
+             "scattered_cost_rule": scattered(700_000, 70, 900),
+             "large_lds": shared_columns(700_000, 300),
+             "late_fallback": shared_columns(700_000, 2400)}
+    for name, A in cases.items():
+        print(f"wide panel case {name}: K={A.K} nnz={A.nnz}", flush=True)
+        plan = make_plan(gpu, A)
+        ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+        assert_format_equal(gpu.spmm_plan_export(plan), ref)
+        got = gpu.spmm_synergy(plan, 8)
+        exp = oracle.synergy(A.M, A.K, 8, A.rowptr, A.colind, ref)
+        for k in INT_KEYS:
+            assert got[k] == exp[k], (k, got[k], exp[k])
+        B = W.dense_b(A.K, 4, 5)
+        Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+        for route in (gpu.ROUTE_AUTO, gpu.ROUTE_VALU):
+            check_c(run_product(gpu, plan, A, B, route=route), Cref, S)
