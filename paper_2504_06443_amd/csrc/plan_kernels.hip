@@ -1,17 +1,20 @@
 // CSR -> brick format on the GPU (paper Section 3.2: active-column compaction,
 // bricks of 4 columns, 64-bit pattern per brick, values packed row-major).
 //
-// All kernels are one-thread-per-entry (or per row / panel / brick) and use no
-// inter-workgroup waiting; the only atomics are integer OR / ADD, so every
-// output is reproducible bit for bit.
+// No kernel waits on another workgroup; the only atomics are integer OR / ADD / MAX,
+// so every output is reproducible bit for bit.
 //
-// The census of active columns avoids sorting: the rows of a panel are already
-// sorted, so "is this the first row of the panel that holds column j" and
-// "how many distinct columns of the panel are smaller than j" are answered by
-// binary searches in the (at most 16) rows of the panel plus one exclusive scan
-// of the first-occurrence flags over the whole entry array.  The second question
-// is only asked once per active column (the first-occurrence entries, compacted
-// into a list); the other entries of that column follow a link to it.
+// Two ways to find a panel's active columns and their ranks, neither of which sorts:
+//  * search-based (any matrix): the rows of a panel are already sorted, so "is this the
+//    first row of the panel that holds column j" and "how many distinct columns of the
+//    panel are smaller than j" are answered by binary searches in the (at most 16) rows of
+//    the panel plus one exclusive scan of the first-occurrence flags over the whole entry
+//    array.  The second question is only asked once per active column (the
+//    first-occurrence entries, compacted into a list); the other entries of that column
+//    follow a link to it.  One thread per entry (or per row / panel / brick).
+//  * per-panel (matrices whose panels span few columns compared with their entries): one
+//    wavefront per panel keeps a bitmap of the panel's column span in LDS; see the section
+//    "per-panel path" below.
 #include "spmm_internal.h"
 
 #include <algorithm>
