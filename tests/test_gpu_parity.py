@@ -391,3 +391,31 @@ def test_plan_paths_for_wide_panels(gpu):
         Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
         for route in (gpu.ROUTE_AUTO, gpu.ROUTE_VALU):
             check_c(run_product(gpu, plan, A, B, route=route), Cref, S)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(gpu, seed):
+    """Seeded random shapes, densities and widths (ragged last panel, empty rows, rows
+    longer than a chunk, N off the vector width): format and counts bit-exact, product
+    within tolerance on the brick kernel, the class-routed mix and the CSR kernel."""
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.integers(1, 400))
+    K = int(rng.integers(1, 3000))
+    density = float(rng.choice([0.002, 0.02, 0.1, 0.5]))
+    N = int(rng.choice([1, 3, 4, 8, 17, 32, 48, 64, 96, 128, 132, 256, 300]))
+    A = W.uniform_random(M, K, density, 7000 + seed, empty_row_frac=float(rng.choice([0.0, 0.3])))
+    print(f"random case seed={seed}: M={M} K={K} nnz={A.nnz} N={N}", flush=True)
+    plan = make_plan(gpu, A)
+    ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+    assert_format_equal(gpu.spmm_plan_export(plan), ref)
+    got = gpu.spmm_synergy(plan, N)
+    exp = oracle.synergy(A.M, A.K, N, A.rowptr, A.colind, ref)
+    for k in INT_KEYS:
+        assert got[k] == exp[k], (k, got[k], exp[k])
+    B = W.dense_b(A.K, N, seed)
+    Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+    for route, split in ((gpu.ROUTE_MFMA, 0), (gpu.ROUTE_MFMA, 2), (gpu.ROUTE_CLASS, 0),
+                         (gpu.ROUTE_VALU, 0)):
+        Cg = run_product(gpu, plan, A, B, route=route, split=split)
+        assert not np.isnan(Cg).any()
+        check_c(Cg, Cref, S)
