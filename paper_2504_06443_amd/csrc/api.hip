@@ -284,7 +284,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   // count is known.  Sub-arrays are 256-byte aligned.
   auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
   Arena scratch, wide, fixed, bricks;
-  uint32_t *d_err, *d_span, *d_maxnb, *scan_tmp, *nbricks_p, *panel_nnzptr;
+  uint32_t *d_err, *d_span, *d_maxnb, *scan_tmp, *nbricks_p, *panel_nnzptr, *ncols_p;
   bool per_panel = false;
   uint32_t h_maxnb = 0;
   uint8_t *col_seen, *panel_class;
@@ -323,7 +323,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(hipDeviceGetAttribute(&pl->num_cus, hipDeviceAttributeMultiprocessorCount, pl->device));
   pl->num_cus = std::max(1, pl->num_cus);
 
-  scratch.cap = need(3, 4) + need(scan_elems, 4) + need(P, 4) + need(P + 1, 4) + need(K, 1) +
+  scratch.cap = need(3, 4) + need(scan_elems, 4) + 2 * need(P, 4) + need(P + 1, 4) + need(K, 1) +
                 need(P, 1) + need(kNumCounters, 8) + need(1, 8);
   HIP_TRY(hipMalloc((void**)&scratch.base, scratch.cap));
   d_err = scratch.take<uint32_t>(3);
@@ -331,6 +331,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   d_maxnb = d_err + 2;
   scan_tmp = scratch.take<uint32_t>(scan_elems);
   nbricks_p = scratch.take<uint32_t>(P);
+  ncols_p = scratch.take<uint32_t>(P);
   panel_nnzptr = scratch.take<uint32_t>(P + 1);
   col_seen = scratch.take<uint8_t>(K);
   panel_class = scratch.take<uint8_t>(P);
@@ -371,7 +372,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
     // ---- per-panel path, a1/a2: census (also validates colind) -> bricks per panel
     HIP_TRY(hipMemsetAsync(d_maxnb, 0, sizeof(uint32_t), s));
     HIP_TRY(launch_panel_census(rowptr, colind, M, K, P, words_cap, d_err, nbricks_p, panel_nnzptr,
-                                d_active, d_maxnb, s));
+                                ncols_p, d_active, d_maxnb, s));
   } else {
     // ---- search-based path for matrices with a panel wider than the LDS bitmap.  Its a1
     // kernels only compare columns, so they may run before the host has seen the verdict of
@@ -408,6 +409,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
     goto done;
   }
 
+  h_maxnb = (h_maxnb + kBrickK - 1) / kBrickK;   // read back as the largest column count of a panel
   if (per_panel && !panel_build_fits(words_cap, std::max<uint32_t>(h_maxnb, 1))) {
     per_panel = false;   // a panel with more bricks than fit in LDS: finish on the search-based path
     status = wide_a1();
@@ -435,7 +437,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
     HIP_TRY(launch_panel_build(rowptr, colind, vals, M, K, P, words_cap,
                                std::max<uint32_t>(h_maxnb, 1), pl->panel_ptr,
                                pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals,
-                               pl->ent_pos, col_seen, panel_class, counters, s));
+                               pl->ent_pos, col_seen, s));
   } else {
     // the arrays of the search-based path, in the order they were carved above
     Arena again = wide;
@@ -456,9 +458,10 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
     HIP_TRY(launch_scan_popc64(pl->brick_mask, pl->nb, pl->brick_valptr, scan_tmp, s));
     HIP_TRY(launch_pack_values(vals, ent_brick, ent_bit, pl->brick_mask, pl->brick_valptr, nnz,
                                pl->vals, pl->ent_pos, s));
-    HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
-    HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
   }
+  // ---- a5: per-panel classes and the synergy counts
+  HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
+  HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
   HIP_TRY(launch_count_flags(col_seen, K, counters + kCntDistinctCols, s));
 
   // ---- host copies for the work-list builder and the model

@@ -462,7 +462,7 @@ __device__ inline void panel_bitmap(const int32_t* __restrict__ colind, const Pa
 __global__ __launch_bounds__(kPanelThreads) void k_panel_census(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind, int64_t M, int64_t K,
     int64_t P, uint32_t words_cap, uint32_t* err, uint32_t* __restrict__ nbricks_p,
-    uint32_t* __restrict__ panel_nnzptr, unsigned long long* n_active, uint32_t* max_nb) {
+    uint32_t* __restrict__ panel_nnzptr, uint32_t* __restrict__ ncols_p) {
   extern __shared__ uint32_t lds[];
   __shared__ int32_t rp[kPanel + 1];
   if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;   // uniform: nothing below is safe
@@ -473,12 +473,12 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_census(
     if (p == P - 1) panel_nnzptr[P] = (uint32_t)x.e1;
   }
   if (x.e0 >= x.e1 || x.cmax < x.cmin) {
-    if (threadIdx.x == 0) nbricks_p[p] = 0;
+    if (threadIdx.x == 0) { nbricks_p[p] = 0; ncols_p[p] = 0; }
     return;
   }
   const uint32_t words = (uint32_t)(x.cmax - x.cmin) / 32u + 1u;
   if (words > words_cap) {   // cannot happen for sorted rows (the cap comes from k_panel_span)
-    if (threadIdx.x == 0) { atomicOr(err, (uint32_t)kErrColOrder); nbricks_p[p] = 0; }
+    if (threadIdx.x == 0) { atomicOr(err, (uint32_t)kErrColOrder); nbricks_p[p] = 0; ncols_p[p] = 0; }
     return;
   }
   panel_bitmap(colind, x, rp, K, words, lds, err);
@@ -487,14 +487,36 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_census(
   uint32_t total;
   wave_exclusive(cnt, &total);
   if (threadIdx.x == 0) {
-    const uint32_t nb = (total + kBrickK - 1) / kBrickK;
-    nbricks_p[p] = nb;
-    atomicAdd(n_active, (unsigned long long)total);
-    atomicMax(max_nb, nb);
+    nbricks_p[p] = (total + kBrickK - 1) / kBrickK;
+    ncols_p[p] = total;
   }
 }
 
-// a2 (placing half), a3, a4 and the a5 counts for one panel.  Dynamic LDS: patterns of the
+// sum and maximum of ncols_p (one atomic pair per workgroup: per-panel atomics on one address
+// serialise at more than 100 ns each)
+__global__ void k_cols_sum_max(const uint32_t* __restrict__ ncols_p, int64_t P,
+                               unsigned long long* sum, uint32_t* max_cols) {
+  __shared__ unsigned long long s_sum;
+  __shared__ uint32_t s_max;
+  if (threadIdx.x == 0) { s_sum = 0; s_max = 0; }
+  __syncthreads();
+  unsigned long long mine = 0;
+  uint32_t mx = 0;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < P; p += stride) {
+    mine += ncols_p[p];
+    mx = max(mx, ncols_p[p]);
+  }
+  if (mine) atomicAdd(&s_sum, mine);
+  if (mx) atomicMax(&s_max, mx);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (s_sum) atomicAdd(sum, s_sum);
+    if (s_max) atomicMax(max_cols, s_max);
+  }
+}
+
+// a2 (placing half), a3 and a4 for one panel.  Dynamic LDS: patterns of the
 // panel's bricks (nb_cap x u64), the bitmap (words_cap words), the coarse rank table
 // (words_cap / 8 + 1 words), value offsets of the panel's bricks (nb_cap words).
 __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
@@ -502,11 +524,9 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
     const float* __restrict__ vals, int64_t M, int64_t K, uint32_t words_cap, uint32_t nb_cap,
     const uint32_t* __restrict__ panel_ptr, uint32_t* __restrict__ brick_cols,
     uint64_t* __restrict__ brick_mask, uint32_t* __restrict__ brick_valptr,
-    float* __restrict__ packed, uint32_t* __restrict__ ent_pos, uint8_t* __restrict__ col_seen,
-    uint8_t* __restrict__ panel_class, unsigned long long* counters) {
+    float* __restrict__ packed, uint32_t* __restrict__ ent_pos, uint8_t* __restrict__ col_seen) {
   extern __shared__ unsigned long long lds64[];
   __shared__ int32_t rp[kPanel + 1];
-  __shared__ uint32_t hist[65];
   unsigned long long* pat = lds64;                                   // [nb_cap]
   uint32_t* bm = reinterpret_cast<uint32_t*>(lds64 + nb_cap);        // [words_cap]
   uint32_t* pre = bm + words_cap;     // [words_cap / 8 + 1]; pre[g] = set bits in words [0, 8g)
@@ -515,13 +535,9 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
   const uint32_t pp = panel_ptr[p];
   const uint32_t nb = panel_ptr[p + 1] - pp;
   const PanelExtent x = panel_extent(rowptr, colind, M, p, rp);
-  if (nb == 0) {
-    if (threadIdx.x == 0) panel_class[p] = 255;
-    return;
-  }
+  if (nb == 0) return;
   const uint32_t words = (uint32_t)(x.cmax - x.cmin) / 32u + 1u;
   for (uint32_t k = threadIdx.x; k < nb; k += kPanelThreads) pat[k] = 0;
-  for (uint32_t t = threadIdx.x; t < 65; t += kPanelThreads) hist[t] = 0;
   panel_bitmap(colind, x, rp, K, words, bm, nullptr);
 
   // coarse rank table: exclusive scan over groups of 8 words, a contiguous run per lane
@@ -582,7 +598,6 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
       const unsigned long long m = pat[k];
       brick_mask[pp + k] = m;
       c = (uint32_t)__popcll(m);
-      atomicAdd(&hist[c], 1u);
     }
     uint32_t total;
     const uint32_t ex = wave_exclusive(c, &total);
@@ -603,18 +618,6 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
     ent_pos[e] = pos;
   }
 
-  // a5: class of the panel (Table 1, integer compare), class totals, popcount histogram
-  if (threadIdx.x == 0) {
-    const unsigned long long nz = (unsigned long long)(x.e1 - x.e0);
-    const uint8_t cls = nz < 8ull * nb ? 0 : (nz < 16ull * nb ? 1 : 2);
-    panel_class[p] = cls;
-    atomicAdd(&counters[kCntPanelsByClass + cls], 1ull);
-    atomicAdd(&counters[kCntBricksByClass + cls], (unsigned long long)nb);
-    atomicAdd(&counters[kCntNnzByClass + cls], nz);
-    atomicAdd(&counters[kCntNonEmptyPanels], 1ull);
-  }
-  for (uint32_t t = threadIdx.x; t < 65; t += kPanelThreads)
-    if (hist[t]) atomicAdd(&counters[kCntPopHist + t], (unsigned long long)hist[t]);
 }
 
 }  // namespace
@@ -773,8 +776,8 @@ bool panel_build_fits(uint32_t words_cap, uint32_t nb_cap) {
 
 hipError_t launch_panel_census(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t K,
                                int64_t P, uint32_t words_cap, uint32_t* err, uint32_t* nbricks_p,
-                               uint32_t* panel_nnzptr, unsigned long long* n_active,
-                               uint32_t* max_nb, hipStream_t s) {
+                               uint32_t* panel_nnzptr, uint32_t* ncols_p,
+                               unsigned long long* n_active, uint32_t* max_cols, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const size_t lds = (size_t)words_cap * 4;
   if (lds > 48 * 1024) {
@@ -783,7 +786,9 @@ hipError_t launch_panel_census(const int32_t* rowptr, const int32_t* colind, int
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(k_panel_census, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr, colind,
-                     M, K, P, words_cap, err, nbricks_p, panel_nnzptr, n_active, max_nb);
+                     M, K, P, words_cap, err, nbricks_p, panel_nnzptr, ncols_p);
+  hipLaunchKernelGGL(k_cols_sum_max, dim3((unsigned)std::min<int64_t>(grid_for(P), 1024)),
+                     dim3(kThreads), 0, s, ncols_p, P, n_active, max_cols);
   return hipGetLastError();
 }
 
@@ -791,8 +796,7 @@ hipError_t launch_panel_build(const int32_t* rowptr, const int32_t* colind, cons
                               int64_t M, int64_t K, int64_t P, uint32_t words_cap, uint32_t nb_cap,
                               const uint32_t* panel_ptr, uint32_t* brick_cols, uint64_t* brick_mask,
                               uint32_t* brick_valptr, float* packed, uint32_t* ent_pos,
-                              uint8_t* col_seen, uint8_t* panel_class, unsigned long long* counters,
-                              hipStream_t s) {
+                              uint8_t* col_seen, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const size_t lds = panel_build_lds(words_cap, nb_cap);
   if (lds > 48 * 1024) {
@@ -802,7 +806,7 @@ hipError_t launch_panel_build(const int32_t* rowptr, const int32_t* colind, cons
   }
   hipLaunchKernelGGL(k_panel_build, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr, colind,
                      vals, M, K, words_cap, nb_cap, panel_ptr, brick_cols, brick_mask, brick_valptr,
-                     packed, ent_pos, col_seen, panel_class, counters);
+                     packed, ent_pos, col_seen);
   return hipGetLastError();
 }
 

@@ -85,15 +85,14 @@ hipError_t launch_panel_span(const int32_t* rowptr, const int32_t* colind, int64
 uint32_t panel_bitmap_words(uint32_t span);   // 0: span too wide for the per-panel path
 hipError_t launch_panel_census(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t K,
                                int64_t P, uint32_t words_cap, uint32_t* err, uint32_t* nbricks_p,
-                               uint32_t* panel_nnzptr, unsigned long long* n_active,
-                               uint32_t* max_nb, hipStream_t s);
+                               uint32_t* panel_nnzptr, uint32_t* ncols_p,
+                               unsigned long long* n_active, uint32_t* max_cols, hipStream_t s);
 bool panel_build_fits(uint32_t words_cap, uint32_t nb_cap);   // LDS of launch_panel_build
 hipError_t launch_panel_build(const int32_t* rowptr, const int32_t* colind, const float* vals,
                               int64_t M, int64_t K, int64_t P, uint32_t words_cap, uint32_t nb_cap,
                               const uint32_t* panel_ptr, uint32_t* brick_cols, uint64_t* brick_mask,
                               uint32_t* brick_valptr, float* packed, uint32_t* ent_pos,
-                              uint8_t* col_seen, uint8_t* panel_class, unsigned long long* counters,
-                              hipStream_t s);
+                              uint8_t* col_seen, hipStream_t s);
 
 // exclusive scans; out has n+1 entries (out[n] = total); tmp holds block sums
 size_t scan_tmp_elems(int64_t n);
