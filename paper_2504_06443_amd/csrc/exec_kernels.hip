@@ -24,8 +24,9 @@
 // and distributed by cross-lane reads.
 //
 // Vector-ALU CSR kernel (the paper's "scalar core" path): one wavefront per
-// row, one coalesced B-row load and one FMA per stored entry.  Used for panels
-// whose brick density is in the Low class of Table 1, and for empty panels.
+// row, one coalesced B-row load and one FMA per stored entry.  Used for empty
+// panels (zero fill) and, under the class-based routing, for panels whose brick
+// density is in the Low class of Table 1.
 #include "spmm_internal.h"
 
 namespace spmm {
