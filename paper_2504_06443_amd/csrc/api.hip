@@ -285,11 +285,12 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
   Arena scratch, wide, fixed, bricks;
   uint32_t *d_err, *d_span, *d_maxnb, *scan_tmp, *nbricks_p, *panel_nnzptr, *ncols_p;
-  bool per_panel = false;
+  enum { kPathSearch, kPathBitmap, kPathSort } path = kPathSearch;
+  uint32_t sort_cap = 0;
   uint32_t h_maxnb = 0;
   uint8_t *col_seen, *panel_class;
   unsigned long long *counters, *d_active;
-  uint32_t h_small[2] = {0, 0};   // error bits, widest panel span
+  uint32_t h_small[3] = {0, 0, 0};   // error bits, widest panel span, most entries of a panel
   uint32_t h_err = 0, h_nb = 0, words_cap = 0;
   unsigned long long h_active = 0;
   const int64_t scan_elems = (int64_t)scan_tmp_elems(std::max(nnz, P + 1));  // bricks <= nnz
@@ -323,12 +324,12 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(hipDeviceGetAttribute(&pl->num_cus, hipDeviceAttributeMultiprocessorCount, pl->device));
   pl->num_cus = std::max(1, pl->num_cus);
 
-  scratch.cap = need(3, 4) + need(scan_elems, 4) + 2 * need(P, 4) + need(P + 1, 4) + need(K, 1) +
+  scratch.cap = need(4, 4) + need(scan_elems, 4) + 2 * need(P, 4) + need(P + 1, 4) + need(K, 1) +
                 need(P, 1) + need(kNumCounters, 8) + need(1, 8);
   HIP_TRY(hipMalloc((void**)&scratch.base, scratch.cap));
-  d_err = scratch.take<uint32_t>(3);
+  d_err = scratch.take<uint32_t>(4);   // error bits, widest span, most entries, most columns
   d_span = d_err + 1;
-  d_maxnb = d_err + 2;
+  d_maxnb = d_err + 3;
   scan_tmp = scratch.take<uint32_t>(scan_elems);
   nbricks_p = scratch.take<uint32_t>(P);
   ncols_p = scratch.take<uint32_t>(P);
@@ -348,11 +349,11 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   pl->ent_pos = fixed.take<uint32_t>(nnz);
 
   // ---- rowptr validation and the widest panel span (device), before anything trusts rowptr
-  HIP_TRY(hipMemsetAsync(d_err, 0, 2 * sizeof(uint32_t), s));
+  HIP_TRY(hipMemsetAsync(d_err, 0, 4 * sizeof(uint32_t), s));
   HIP_TRY(hipMemsetAsync(d_active, 0, sizeof(unsigned long long), s));
   HIP_TRY(launch_validate_rowptr(rowptr, M, nnz, d_err, s));
   HIP_TRY(launch_panel_span(rowptr, colind, M, P, d_err, d_span, s));
-  HIP_TRY(hipMemcpyAsync(h_small, d_err, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(h_small, d_err, 3 * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
   h_err = h_small[0];
   if (h_err & (kErrRowptrEnds | kErrRowptrOrder)) {
@@ -362,17 +363,26 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   }
   words_cap = panel_bitmap_words(h_small[1]);
 
-  // The per-panel kernels walk a bitmap over the panel's column span; that pays while the
-  // bitmaps are not much longer than the entry lists (band-like matrices).  Scattered
-  // matrices (power-law graphs, random bricks: spans near K) take the search-based kernels.
-  // Measured: config 5 (bitmap words x panels = 4 x nnz) 0.6 vs 1.0 ms in favour of the
-  // bitmap, config 3 (360 x) 4.0 vs 0.9 ms and the 1M-row sweep (67 x) 31 vs 3.8 ms against it.
-  per_panel = words_cap != 0 && (int64_t)words_cap * P <= 8 * nnz;
-  if (per_panel) {
-    // ---- per-panel path, a1/a2: census (also validates colind) -> bricks per panel
-    HIP_TRY(hipMemsetAsync(d_maxnb, 0, sizeof(uint32_t), s));
+  // Three ways to the same format.  The bitmap kernels walk a bitmap over the panel's column
+  // span; that pays while the bitmaps are not much longer than the entry lists (band-like
+  // matrices).  Scattered matrices (power-law graphs, random bricks: spans near K) sort each
+  // panel's entries in LDS instead when panels are well filled and none is large (the sort
+  // costs a fixed network per panel and LDS per wavefront); everything else takes the
+  // search-based kernels.  Measured: config 5 (bitmap words x panels = 4 x nnz) 0.6 vs 1.0 ms
+  // (search) in favour of the bitmap, config 3 (360 x) 4.0 vs 0.9 ms and the 1M-row sweep
+  // (67 x) 31 vs 3.8 ms against it; sort against search: 1M-row sweep f = 0.4 (488 entries
+  // per panel) 2.4 vs 4.5 ms, f = 0.8 3.8 vs 3.8 ms, config 3 (46 per panel, largest 3000+)
+  // 1.45 vs 0.99 ms.
+  sort_cap = panel_sort_keys(h_small[2]);
+  if (words_cap != 0 && (int64_t)words_cap * P <= 8 * nnz) path = kPathBitmap;
+  else if (sort_cap != 0 && sort_cap <= 2048 && nnz >= 128 * P) path = kPathSort;
+  if (path == kPathBitmap) {
+    // ---- a1/a2: census (also validates colind) -> bricks per panel
     HIP_TRY(launch_panel_census(rowptr, colind, M, K, P, words_cap, d_err, nbricks_p, panel_nnzptr,
                                 ncols_p, d_active, d_maxnb, s));
+  } else if (path == kPathSort) {
+    HIP_TRY(launch_panel_sort_census(rowptr, colind, M, K, P, sort_cap, d_err, nbricks_p,
+                                     panel_nnzptr, ncols_p, d_active, d_maxnb, s));
   } else {
     // ---- search-based path for matrices with a panel wider than the LDS bitmap.  Its a1
     // kernels only compare columns, so they may run before the host has seen the verdict of
@@ -384,7 +394,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(hipMemcpyAsync(&h_nb, pl->panel_ptr + P, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipMemcpyAsync(&h_active, d_active, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipMemcpyAsync(&h_err, d_err, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-  if (per_panel)
+  if (path != kPathSearch)
     HIP_TRY(hipMemcpyAsync(&h_maxnb, d_maxnb, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
   // plan-owned CSR copy for the vector-ALU kernel, while the host waits for the counts
   HIP_TRY(hipMemcpyAsync(pl->rowptr, rowptr, (size_t)(M + 1) * sizeof(int32_t),
@@ -410,8 +420,9 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   }
 
   h_maxnb = (h_maxnb + kBrickK - 1) / kBrickK;   // read back as the largest column count of a panel
-  if (per_panel && !panel_build_fits(words_cap, std::max<uint32_t>(h_maxnb, 1))) {
-    per_panel = false;   // a panel with more bricks than fit in LDS: finish on the search-based path
+  if ((path == kPathBitmap && !panel_build_fits(words_cap, std::max<uint32_t>(h_maxnb, 1))) ||
+      (path == kPathSort && !panel_sort_build_fits(sort_cap, std::max<uint32_t>(h_maxnb, 1)))) {
+    path = kPathSearch;   // a panel with more bricks than fit in LDS: finish on the search-based path
     status = wide_a1();
     if (status != SPMM_OK) goto done;
   }
@@ -432,8 +443,13 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(hipMemsetAsync(col_seen, 0, (size_t)std::max<int64_t>(K, 1), s));
   HIP_TRY(hipMemsetAsync(counters, 0, kNumCounters * sizeof(unsigned long long), s));
 
-  if (per_panel) {
-    // ---- a2 (placing), a3, a4 and the per-panel part of a5, one wavefront per panel
+  if (path == kPathSort) {
+    HIP_TRY(launch_panel_sort_build(rowptr, colind, vals, M, K, P, sort_cap,
+                                    std::max<uint32_t>(h_maxnb, 1), pl->panel_ptr, pl->brick_cols,
+                                    pl->brick_mask, pl->brick_valptr, pl->vals, pl->ent_pos,
+                                    col_seen, s));
+  } else if (path == kPathBitmap) {
+    // ---- a2 (placing), a3, a4, one wavefront per panel
     HIP_TRY(launch_panel_build(rowptr, colind, vals, M, K, P, words_cap,
                                std::max<uint32_t>(h_maxnb, 1), pl->panel_ptr,
                                pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals,

@@ -365,6 +365,7 @@ constexpr int kPanelThreads = 64;
 constexpr int kGroupWords = 8;   // bitmap words per entry of the coarse rank table
 constexpr uint32_t kPanelMaxWords = 32768;          // 1 Mi columns of span
 constexpr size_t kPanelMaxLds = 150 * 1024;         // of the 160 KiB of a CU
+constexpr uint32_t kPanelMaxSortKeys = 8192;        // entries of a panel on the sort-based path
 
 struct PanelExtent {
   int64_t e0, e1;        // entries of the panel
@@ -418,19 +419,31 @@ __device__ inline int row_in_panel(const int32_t* rp, int64_t e) {
   return r;
 }
 
-// widest column span of any panel (0 for an empty matrix); requires a valid rowptr
+// widest column span and largest entry count of any panel (0 for an empty matrix); requires
+// a valid rowptr.  out[0] = span, out[1] = entries.
 __global__ void k_panel_span(const int32_t* __restrict__ rowptr,
                              const int32_t* __restrict__ colind, int64_t M, int64_t P,
-                             const uint32_t* __restrict__ err, uint32_t* max_span) {
+                             const uint32_t* __restrict__ err, uint32_t* out) {
+  __shared__ uint32_t s_span, s_nnz;
   if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;
+  if (threadIdx.x == 0) { s_span = 0; s_nnz = 0; }
+  __syncthreads();
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= P) return;
-  int32_t lo = 0x7FFFFFFF, hi = -1;
-  for (int64_t r = p * kPanel; r < min((p + 1) * kPanel, M); ++r) {
-    const int32_t s = rowptr[r], t = rowptr[r + 1];
-    if (s < t) { lo = min(lo, colind[s]); hi = max(hi, colind[t - 1]); }
+  if (p < P) {
+    int32_t lo = 0x7FFFFFFF, hi = -1;
+    const int64_t r0 = p * kPanel, r1 = min((p + 1) * kPanel, M);
+    for (int64_t r = r0; r < r1; ++r) {
+      const int32_t s = rowptr[r], t = rowptr[r + 1];
+      if (s < t) { lo = min(lo, colind[s]); hi = max(hi, colind[t - 1]); }
+    }
+    if (hi >= lo) atomicMax(&s_span, (uint32_t)((int64_t)hi - lo + 1));
+    atomicMax(&s_nnz, (uint32_t)(rowptr[r1] - rowptr[r0]));
   }
-  if (hi >= lo) atomicMax(max_span, (uint32_t)((int64_t)hi - lo + 1));
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (s_span) atomicMax(&out[0], s_span);
+    if (s_nnz) atomicMax(&out[1], s_nnz);
+  }
 }
 
 // sets the panel's bitmap; checks the columns on the way (range, order, inside the span)
@@ -492,6 +505,177 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_census(
   }
 }
 
+// ---- per-panel path for scattered matrices: sort instead of a bitmap
+// One wavefront per panel sorts the panel's entries by (column, entry) in LDS (bitonic network
+// on 64-bit keys: column in the high half, entry index inside the panel in the low half).
+// Equal columns end up next to each other: flags + a scan give the rank of every column, with
+// no dependence on the width of the panel's column span.
+// Loads the keys (padded with all-ones to n_sort, a power of two >= 64), checks the columns,
+// sorts ascending.
+__device__ inline void panel_sort(const int32_t* __restrict__ colind, const PanelExtent& x,
+                                  const int32_t* rp, int64_t K, uint32_t n_sort,
+                                  unsigned long long* keys, uint32_t* err) {
+  const uint32_t n = (uint32_t)(x.e1 - x.e0);
+  uint32_t bad = 0;
+  for (uint32_t i = threadIdx.x; i < n_sort; i += kPanelThreads) {
+    unsigned long long key = ~0ull;
+    if (i < n) {
+      const int64_t e = x.e0 + i;
+      const int32_t j = colind[e];
+      if (err) {
+        if (j < 0 || j >= K) bad |= kErrColRange;
+        if (e > rp[row_in_panel(rp, e)] && colind[e - 1] >= j) bad |= kErrColOrder;
+      }
+      key = ((unsigned long long)(uint32_t)j << 32) | i;
+    }
+    keys[i] = key;
+  }
+  if (err && bad) atomicOr(err, bad);
+  __syncthreads();
+  for (uint32_t k = 2; k <= n_sort; k <<= 1) {
+    for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+      for (uint32_t i = threadIdx.x; i < n_sort / 2; i += kPanelThreads) {
+        const uint32_t a = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+        const uint32_t b = a | j;
+        const unsigned long long ka = keys[a], kb = keys[b];
+        const bool ascending = (a & k) == 0;
+        if ((ka > kb) == ascending) { keys[a] = kb; keys[b] = ka; }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+__device__ inline uint32_t sort_size(uint32_t n) {
+  uint32_t m = 64;
+  while (m < n) m <<= 1;
+  return m;
+}
+
+// census by sorting: distinct columns of each panel; validates colind.  Dynamic LDS: keys.
+__global__ __launch_bounds__(kPanelThreads) void k_panel_sort_census(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind, int64_t M, int64_t K,
+    int64_t P, uint32_t n_cap, uint32_t* err, uint32_t* __restrict__ nbricks_p,
+    uint32_t* __restrict__ panel_nnzptr, uint32_t* __restrict__ ncols_p) {
+  extern __shared__ unsigned long long lds64[];
+  __shared__ int32_t rp[kPanel + 1];
+  if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;   // uniform: nothing below is safe
+  const int64_t p = blockIdx.x;
+  const PanelExtent x = panel_extent(rowptr, colind, M, p, rp);
+  if (threadIdx.x == 0) {
+    panel_nnzptr[p] = (uint32_t)x.e0;
+    if (p == P - 1) panel_nnzptr[P] = (uint32_t)x.e1;
+  }
+  const uint32_t n = (uint32_t)(x.e1 - x.e0);
+  if (n == 0 || n > n_cap) {   // (n > n_cap cannot happen: the cap comes from k_panel_span)
+    if (threadIdx.x == 0) { nbricks_p[p] = 0; ncols_p[p] = 0; }
+    return;
+  }
+  panel_sort(colind, x, rp, K, sort_size(n), lds64, err);
+  uint32_t cnt = 0;
+  for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads)
+    cnt += (i == 0 || (uint32_t)(lds64[i] >> 32) != (uint32_t)(lds64[i - 1] >> 32)) ? 1u : 0u;
+  uint32_t total;
+  wave_exclusive(cnt, &total);
+  if (threadIdx.x == 0) {
+    nbricks_p[p] = (total + kBrickK - 1) / kBrickK;
+    ncols_p[p] = total;
+  }
+}
+
+// a2 (placing half), a3 and a4 for one panel, by sorting.  Dynamic LDS: keys (n_cap x u64),
+// patterns (nb_cap x u64), value offsets (nb_cap words).
+__global__ __launch_bounds__(kPanelThreads) void k_panel_sort_build(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
+    const float* __restrict__ vals, int64_t M, int64_t K, uint32_t n_cap, uint32_t nb_cap,
+    const uint32_t* __restrict__ panel_ptr, uint32_t* __restrict__ brick_cols,
+    uint64_t* __restrict__ brick_mask, uint32_t* __restrict__ brick_valptr,
+    float* __restrict__ packed, uint32_t* __restrict__ ent_pos, uint8_t* __restrict__ col_seen) {
+  extern __shared__ unsigned long long lds64[];
+  __shared__ int32_t rp[kPanel + 1];
+  unsigned long long* keys = lds64;                                  // [n_cap]
+  unsigned long long* pat = lds64 + n_cap;                           // [nb_cap]
+  uint32_t* vptr = reinterpret_cast<uint32_t*>(pat + nb_cap);        // [nb_cap]
+  const int64_t p = blockIdx.x;
+  const uint32_t pp = panel_ptr[p];
+  const uint32_t nb = panel_ptr[p + 1] - pp;
+  const PanelExtent x = panel_extent(rowptr, colind, M, p, rp);
+  if (nb == 0) return;
+  const uint32_t n = (uint32_t)(x.e1 - x.e0);
+  if (n > n_cap || nb > nb_cap) return;   // (cannot happen: both caps are maxima over the panels)
+  for (uint32_t k = threadIdx.x; k < nb; k += kPanelThreads) pat[k] = 0;
+  panel_sort(colind, x, rp, K, sort_size(n), keys, nullptr);
+
+  // rank of each sorted entry's column = number of column changes before it; first
+  // occurrences write brick_cols; then the key's column is replaced by the rank.  The column
+  // before a batch of 64 is carried in a register: its key has been rewritten by then.
+  uint32_t carry = 0;
+  uint32_t col_before = 0xFFFFFFFFu;   // never a column (columns are below 2^31)
+  for (uint32_t base = 0; base < n; base += kPanelThreads) {
+    const uint32_t i = base + threadIdx.x;
+    uint32_t col = 0xFFFFFFFFu, first = 0;
+    if (i < n) col = (uint32_t)(keys[i] >> 32);
+    uint32_t prev = __shfl_up(col, 1, 64);
+    if (threadIdx.x == 0) prev = col_before;
+    if (i < n) first = (col != prev) ? 1u : 0u;
+    uint32_t total;
+    const uint32_t ex = wave_exclusive(first, &total);
+    if (i < n) {
+      const uint32_t rank = carry + ex + first - 1u;   // inclusive count of firsts, minus one
+      if (first && rank < nb * kBrickK) {
+        brick_cols[(int64_t)pp * kBrickK + rank] = col;
+        col_seen[col] = 1;
+      }
+      keys[i] = ((unsigned long long)rank << 32) | (uint32_t)keys[i];
+    }
+    col_before = __shfl(col, 63, 64);
+    carry += total;
+  }
+  __syncthreads();
+  for (uint32_t k = carry + threadIdx.x; k < nb * kBrickK; k += kPanelThreads)
+    brick_cols[(int64_t)pp * kBrickK + k] = kPadCol;
+
+  // a3: pattern bits, accumulated in LDS
+  for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads) {
+    const uint32_t rank = (uint32_t)(keys[i] >> 32);
+    const int64_t e = x.e0 + (uint32_t)keys[i];
+    const uint32_t bit = (uint32_t)row_in_panel(rp, e) * kBrickK + rank % kBrickK;
+    if (rank / kBrickK < nb) atomicOr(&pat[rank / kBrickK], 1ull << bit);
+  }
+  __syncthreads();
+
+  // a4: value offsets = entries before the panel + popcounts of the panel's earlier bricks
+  uint32_t off = (uint32_t)x.e0;
+  for (uint32_t base = 0; base < nb; base += kPanelThreads) {
+    const uint32_t k = base + threadIdx.x;
+    uint32_t c = 0;
+    if (k < nb) {
+      const unsigned long long m = pat[k];
+      brick_mask[pp + k] = m;
+      c = (uint32_t)__popcll(m);
+    }
+    uint32_t total;
+    const uint32_t ex = wave_exclusive(c, &total);
+    if (k < nb) {
+      vptr[k] = off + ex;
+      brick_valptr[pp + k] = off + ex;
+    }
+    off += total;
+  }
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads) {
+    const uint32_t rank = (uint32_t)(keys[i] >> 32);
+    const int64_t e = x.e0 + (uint32_t)keys[i];
+    const uint32_t bit = (uint32_t)row_in_panel(rp, e) * kBrickK + rank % kBrickK;
+    const uint32_t k = min(rank / kBrickK, nb - 1);
+    const uint32_t pos = vptr[k] + (uint32_t)__popcll(pat[k] & ((1ull << bit) - 1ull));
+    if (pos < (uint32_t)x.e1) {   // (always, for a census and a build that agree)
+      packed[pos] = vals[e];
+      ent_pos[e] = pos;
+    }
+  }
+}
+
 // sum and maximum of ncols_p (one atomic pair per workgroup: per-panel atomics on one address
 // serialise at more than 100 ns each)
 __global__ void k_cols_sum_max(const uint32_t* __restrict__ ncols_p, int64_t P,
@@ -537,6 +721,7 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
   const PanelExtent x = panel_extent(rowptr, colind, M, p, rp);
   if (nb == 0) return;
   const uint32_t words = (uint32_t)(x.cmax - x.cmin) / 32u + 1u;
+  if (words > words_cap || nb > nb_cap) return;   // (cannot happen: both caps are maxima)
   for (uint32_t k = threadIdx.x; k < nb; k += kPanelThreads) pat[k] = 0;
   panel_bitmap(colind, x, rp, K, words, bm, nullptr);
 
@@ -585,7 +770,7 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
     const uint32_t d = (uint32_t)(colind[e] - x.cmin);
     const uint32_t rank = bits_before_word(d >> 5) + __popc(bm[d >> 5] & ((1u << (d & 31)) - 1u));
     const uint32_t bit = (uint32_t)row_in_panel(rp, e) * kBrickK + rank % kBrickK;
-    atomicOr(&pat[rank / kBrickK], 1ull << bit);
+    if (rank / kBrickK < nb) atomicOr(&pat[rank / kBrickK], 1ull << bit);
   }
   __syncthreads();
 
@@ -612,12 +797,13 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_build(
     const uint32_t d = (uint32_t)(colind[e] - x.cmin);
     const uint32_t rank = bits_before_word(d >> 5) + __popc(bm[d >> 5] & ((1u << (d & 31)) - 1u));
     const uint32_t bit = (uint32_t)row_in_panel(rp, e) * kBrickK + rank % kBrickK;
-    const uint32_t k = rank / kBrickK;
+    const uint32_t k = min(rank / kBrickK, nb - 1);
     const uint32_t pos = vptr[k] + (uint32_t)__popcll(pat[k] & ((1ull << bit) - 1ull));
-    packed[pos] = vals[e];
-    ent_pos[e] = pos;
+    if (pos < (uint32_t)x.e1) {   // (always, for a census and a build that agree)
+      packed[pos] = vals[e];
+      ent_pos[e] = pos;
+    }
   }
-
 }
 
 }  // namespace
@@ -751,10 +937,61 @@ hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long lon
 
 // ---- per-panel path
 hipError_t launch_panel_span(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t P,
-                             const uint32_t* err, uint32_t* max_span, hipStream_t s) {
+                             const uint32_t* err, uint32_t* span_and_nnz, hipStream_t s) {
   if (P == 0) return hipSuccess;
   hipLaunchKernelGGL(k_panel_span, dim3(grid_for(P)), dim3(kThreads), 0, s, rowptr, colind, M, P,
-                     err, max_span);
+                     err, span_and_nnz);
+  return hipGetLastError();
+}
+
+// ---- sort-based per-panel path
+// keys of the sort for panels of up to max_nnz entries (a power of two), or 0 if too many
+uint32_t panel_sort_keys(uint32_t max_nnz) {
+  uint32_t n = 64;
+  while (n < max_nnz && n < kPanelMaxSortKeys) n *= 2;
+  return n >= max_nnz ? n : 0;
+}
+static size_t panel_sort_build_lds(uint32_t n_cap, uint32_t nb_cap) {
+  return (size_t)n_cap * 8 + (size_t)nb_cap * 12;
+}
+bool panel_sort_build_fits(uint32_t n_cap, uint32_t nb_cap) {
+  return n_cap != 0 && panel_sort_build_lds(n_cap, nb_cap) <= kPanelMaxLds;
+}
+
+hipError_t launch_panel_sort_census(const int32_t* rowptr, const int32_t* colind, int64_t M,
+                                    int64_t K, int64_t P, uint32_t n_cap, uint32_t* err,
+                                    uint32_t* nbricks_p, uint32_t* panel_nnzptr, uint32_t* ncols_p,
+                                    unsigned long long* n_active, uint32_t* max_cols,
+                                    hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t lds = (size_t)n_cap * 8;
+  if (lds > 48 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_panel_sort_census),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_panel_sort_census, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr,
+                     colind, M, K, P, n_cap, err, nbricks_p, panel_nnzptr, ncols_p);
+  hipLaunchKernelGGL(k_cols_sum_max, dim3((unsigned)std::min<int64_t>(grid_for(P), 1024)),
+                     dim3(kThreads), 0, s, ncols_p, P, n_active, max_cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_panel_sort_build(const int32_t* rowptr, const int32_t* colind, const float* vals,
+                                   int64_t M, int64_t K, int64_t P, uint32_t n_cap, uint32_t nb_cap,
+                                   const uint32_t* panel_ptr, uint32_t* brick_cols,
+                                   uint64_t* brick_mask, uint32_t* brick_valptr, float* packed,
+                                   uint32_t* ent_pos, uint8_t* col_seen, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t lds = panel_sort_build_lds(n_cap, nb_cap);
+  if (lds > 48 * 1024) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_panel_sort_build),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_panel_sort_build, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr,
+                     colind, vals, M, K, n_cap, nb_cap, panel_ptr, brick_cols, brick_mask,
+                     brick_valptr, packed, ent_pos, col_seen);
   return hipGetLastError();
 }
 

@@ -80,8 +80,22 @@ hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long lon
                               hipStream_t s);
 
 // per-panel path (LDS bitmap over the panel's column span)
+// out[0] = widest column span of a panel, out[1] = most entries of a panel
 hipError_t launch_panel_span(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t P,
-                             const uint32_t* err, uint32_t* max_span, hipStream_t s);
+                             const uint32_t* err, uint32_t* span_and_nnz, hipStream_t s);
+// per-panel path by sorting (any column span, panels of limited size)
+uint32_t panel_sort_keys(uint32_t max_nnz);   // 0: a panel has too many entries
+bool panel_sort_build_fits(uint32_t n_cap, uint32_t nb_cap);
+hipError_t launch_panel_sort_census(const int32_t* rowptr, const int32_t* colind, int64_t M,
+                                    int64_t K, int64_t P, uint32_t n_cap, uint32_t* err,
+                                    uint32_t* nbricks_p, uint32_t* panel_nnzptr, uint32_t* ncols_p,
+                                    unsigned long long* n_active, uint32_t* max_cols,
+                                    hipStream_t s);
+hipError_t launch_panel_sort_build(const int32_t* rowptr, const int32_t* colind, const float* vals,
+                                   int64_t M, int64_t K, int64_t P, uint32_t n_cap, uint32_t nb_cap,
+                                   const uint32_t* panel_ptr, uint32_t* brick_cols,
+                                   uint64_t* brick_mask, uint32_t* brick_valptr, float* packed,
+                                   uint32_t* ent_pos, uint8_t* col_seen, hipStream_t s);
 uint32_t panel_bitmap_words(uint32_t span);   // 0: span too wide for the per-panel path
 hipError_t launch_panel_census(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t K,
                                int64_t P, uint32_t words_cap, uint32_t* err, uint32_t* nbricks_p,

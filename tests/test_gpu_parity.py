@@ -353,12 +353,14 @@ def test_update_values_keeps_pattern_and_replaces_values(gpu, name):
 
 
 def test_plan_paths_for_wide_panels(gpu):
-    """The plan has a per-panel path (bitmap of the panel's column span in LDS) and a
-    search-based one.  Cases: a span beyond the largest bitmap (search-based); a scattered
-    matrix whose bitmaps would dwarf its entry lists (search-based by the cost rule); one panel
-    with a 700k-column span and many entries (per-panel, LDS allocation above the default
-    limit); the same with more bricks than LDS holds beside that bitmap (starts per-panel,
-    finishes search-based).  All must give the oracle's format, counts and product."""
+    """The plan has two per-panel paths (a bitmap of the panel's column span in LDS; a sort of
+    the panel's entries in LDS) and a search-based one.  Cases: a span beyond the largest bitmap
+    and a scattered matrix whose bitmaps would dwarf its entry lists (both sorted); one panel
+    with a 700k-column span and many entries (bitmap, LDS allocation above the default limit);
+    the same with more bricks than LDS holds beside that bitmap (starts on the bitmap path,
+    finishes search-based); a span beyond the bitmap with more entries in one panel than the
+    sort holds (search-based from the start).  All must give the oracle's format, counts and
+    product."""
     rng = np.random.default_rng(77)
 
     def scattered(K, M, n):
@@ -374,10 +376,11 @@ def test_plan_paths_for_wide_panels(gpu):
         return W.csr_from_coo(16, K, rows, np.tile(cols, 16),
                               rng.uniform(-1, 1, 16 * ncols).astype(np.float32))
 
-    cases = {"beyond_bitmap": scattered(1_300_000, 70, 900),
-             "scattered_cost_rule": scattered(700_000, 70, 900),
-             "large_lds": shared_columns(700_000, 300),
-             "late_fallback": shared_columns(700_000, 2400)}
+    cases = {"beyond_bitmap": scattered(1_300_000, 70, 900),            # sorted per panel
+             "scattered_cost_rule": scattered(700_000, 70, 900),       # sorted per panel
+             "large_lds": shared_columns(700_000, 300),                # bitmap, large LDS
+             "late_fallback": shared_columns(700_000, 2400),           # bitmap, then searches
+             "search_path": shared_columns(1_300_000, 600)}            # searches from the start
     for name, A in cases.items():
         print(f"wide panel case {name}: K={A.K} nnz={A.nnz}", flush=True)
         plan = make_plan(gpu, A)
