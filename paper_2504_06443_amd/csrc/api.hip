@@ -382,7 +382,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
                                 ncols_p, d_active, d_maxnb, s));
   } else if (path == kPathSort) {
     HIP_TRY(launch_panel_sort_census(rowptr, colind, M, K, P, sort_cap, d_err, nbricks_p,
-                                     panel_nnzptr, ncols_p, d_active, d_maxnb, s));
+                                     panel_nnzptr, ncols_p, pl->ent_pos, d_active, d_maxnb, s));
   } else {
     // ---- search-based path for matrices with a panel wider than the LDS bitmap.  Its a1
     // kernels only compare columns, so they may run before the host has seen the verdict of

@@ -552,11 +552,13 @@ __device__ inline uint32_t sort_size(uint32_t n) {
   return m;
 }
 
-// census by sorting: distinct columns of each panel; validates colind.  Dynamic LDS: keys.
+// census by sorting: distinct columns of each panel; validates colind; leaves the sorted order
+// of each panel's entries (indices inside the panel) in `order`.  Dynamic LDS: keys.
 __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_census(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind, int64_t M, int64_t K,
     int64_t P, uint32_t n_cap, uint32_t* err, uint32_t* __restrict__ nbricks_p,
-    uint32_t* __restrict__ panel_nnzptr, uint32_t* __restrict__ ncols_p) {
+    uint32_t* __restrict__ panel_nnzptr, uint32_t* __restrict__ ncols_p,
+    uint32_t* __restrict__ order) {
   extern __shared__ unsigned long long lds64[];
   __shared__ int32_t rp[kPanel + 1];
   if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;   // uniform: nothing below is safe
@@ -573,8 +575,10 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_census(
   }
   panel_sort(colind, x, rp, K, sort_size(n), lds64, err);
   uint32_t cnt = 0;
-  for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads)
+  for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads) {
     cnt += (i == 0 || (uint32_t)(lds64[i] >> 32) != (uint32_t)(lds64[i - 1] >> 32)) ? 1u : 0u;
+    order[x.e0 + i] = (uint32_t)lds64[i];   // sorted order of the panel's entries, for the build
+  }
   uint32_t total;
   wave_exclusive(cnt, &total);
   if (threadIdx.x == 0) {
@@ -583,14 +587,15 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_census(
   }
 }
 
-// a2 (placing half), a3 and a4 for one panel, by sorting.  Dynamic LDS: keys (n_cap x u64),
-// patterns (nb_cap x u64), value offsets (nb_cap words).
+// a2 (placing half), a3 and a4 for one panel from the sorted order left by the census in
+// `ent_pos` (which this kernel then overwrites with the value positions).  Dynamic LDS: keys
+// (n_cap x u64), patterns (nb_cap x u64), value offsets (nb_cap words).
 __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_build(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
     const float* __restrict__ vals, int64_t M, int64_t K, uint32_t n_cap, uint32_t nb_cap,
     const uint32_t* __restrict__ panel_ptr, uint32_t* __restrict__ brick_cols,
     uint64_t* __restrict__ brick_mask, uint32_t* __restrict__ brick_valptr,
-    float* __restrict__ packed, uint32_t* __restrict__ ent_pos, uint8_t* __restrict__ col_seen) {
+    float* __restrict__ packed, uint32_t* ent_pos, uint8_t* __restrict__ col_seen) {
   extern __shared__ unsigned long long lds64[];
   __shared__ int32_t rp[kPanel + 1];
   unsigned long long* keys = lds64;                                  // [n_cap]
@@ -604,7 +609,11 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_build(
   const uint32_t n = (uint32_t)(x.e1 - x.e0);
   if (n > n_cap || nb > nb_cap) return;   // (cannot happen: both caps are maxima over the panels)
   for (uint32_t k = threadIdx.x; k < nb; k += kPanelThreads) pat[k] = 0;
-  panel_sort(colind, x, rp, K, sort_size(n), keys, nullptr);
+  for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads) {
+    const uint32_t idx = min(ent_pos[x.e0 + i], n - 1);   // (always below n)
+    keys[i] = ((unsigned long long)(uint32_t)colind[x.e0 + idx] << 32) | idx;
+  }
+  __syncthreads();
 
   // rank of each sorted entry's column = number of column changes before it; first
   // occurrences write brick_cols; then the key's column is replaced by the rank.  The column
@@ -961,8 +970,8 @@ bool panel_sort_build_fits(uint32_t n_cap, uint32_t nb_cap) {
 hipError_t launch_panel_sort_census(const int32_t* rowptr, const int32_t* colind, int64_t M,
                                     int64_t K, int64_t P, uint32_t n_cap, uint32_t* err,
                                     uint32_t* nbricks_p, uint32_t* panel_nnzptr, uint32_t* ncols_p,
-                                    unsigned long long* n_active, uint32_t* max_cols,
-                                    hipStream_t s) {
+                                    uint32_t* order, unsigned long long* n_active,
+                                    uint32_t* max_cols, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const size_t lds = (size_t)n_cap * 8;
   if (lds > 48 * 1024) {
@@ -971,7 +980,7 @@ hipError_t launch_panel_sort_census(const int32_t* rowptr, const int32_t* colind
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(k_panel_sort_census, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr,
-                     colind, M, K, P, n_cap, err, nbricks_p, panel_nnzptr, ncols_p);
+                     colind, M, K, P, n_cap, err, nbricks_p, panel_nnzptr, ncols_p, order);
   hipLaunchKernelGGL(k_cols_sum_max, dim3((unsigned)std::min<int64_t>(grid_for(P), 1024)),
                      dim3(kThreads), 0, s, ncols_p, P, n_active, max_cols);
   return hipGetLastError();

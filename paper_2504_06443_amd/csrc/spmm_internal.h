@@ -89,6 +89,7 @@ bool panel_sort_build_fits(uint32_t n_cap, uint32_t nb_cap);
 hipError_t launch_panel_sort_census(const int32_t* rowptr, const int32_t* colind, int64_t M,
                                     int64_t K, int64_t P, uint32_t n_cap, uint32_t* err,
                                     uint32_t* nbricks_p, uint32_t* panel_nnzptr, uint32_t* ncols_p,
+                                    uint32_t* order /* [nnz]; read back by the build as ent_pos */,
                                     unsigned long long* n_active, uint32_t* max_cols,
                                     hipStream_t s);
 hipError_t launch_panel_sort_build(const int32_t* rowptr, const int32_t* colind, const float* vals,

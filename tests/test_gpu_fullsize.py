@@ -77,6 +77,13 @@ def test_config5_sweep(gpu, fill):
         check_full(gpu, A, N, f"config5 f={fill}", check_format=(N == 16), routes=("mfma", "valu"))
 
 
+def test_scattered_sweep_takes_the_sort_path(gpu):
+    """Random 16x4 cells over 262144 columns, 244 entries per panel: too scattered for the
+    plan's bitmap path, well filled enough for its per-panel sort.  Format bit-exact."""
+    A = W.brick_sweep(0.4, M=1 << 18, target_nnz=4_000_000, seed=77)
+    check_full(gpu, A, 64, "scattered sweep", check_format=True, routes=("mfma",))
+
+
 def test_config4_fem(gpu):
     A, Ns = W.config(4)
     for N in Ns:
