@@ -422,3 +422,32 @@ def test_random_shapes(gpu, seed):
         Cg = run_product(gpu, plan, A, B, route=route, split=split)
         assert not np.isnan(Cg).any()
         check_c(Cg, Cref, S)
+
+
+def test_plans_release_their_memory(gpu):
+    """Creating, using and destroying plans in a loop (all three plan paths, work lists with
+    split panels) must not accumulate device memory."""
+    import torch
+    mats = [W.clustered_blocks(3000, 6, 90, seed=1), W.power_law(M=2000, target_nnz=None, cap=800, seed=2),
+            W.brick_sweep(0.4, M=4096, target_nnz=120_000, seed=3)]
+    def cycle():
+        for A in mats:
+            plan = make_plan(gpu, A)
+            B = torch.zeros((A.K, 32), device="cuda")
+            gpu.spmm_plan_set_split(plan, 2)
+            gpu.spmm_exec(plan, B)
+            gpu.spmm_plan_set_split(plan, 0)
+            gpu.spmm_exec(plan, B)
+            torch.cuda.synchronize()
+            plan.destroy()
+            del B
+    cycle()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(30):
+        cycle()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 8 << 20, f"device memory shrank by {(free0 - free1) >> 20} MiB over 90 plans"
