@@ -170,7 +170,9 @@ int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** ou
   for (int64_t p = 0; p < pl->P; ++p) {
     const uint8_t cls = pl->h_panel_class[p];
     bool to_mfma;
-    if (cls == 255) to_mfma = false;  // empty panel: the CSR kernel stores its zero rows
+    // an empty panel only needs its rows of C zeroed; either kernel does that, so it goes
+    // where the other panels go and does not cost a second launch
+    if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_AUTO || pl->route == SPMM_ROUTE_MFMA;
     else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
     else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
     else if (pl->route == SPMM_ROUTE_CLASS) to_mfma = cls != SPMM_LOW;
@@ -207,10 +209,10 @@ int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** ou
     const uint32_t b0 = pl->h_panel_ptr[p];
     const int64_t nbp = nbricks[i];
     const int64_t blocks = ceil_div(nbp, kBrickK);
-    const int64_t want = std::min<int64_t>(parts[i], blocks);
-    const int64_t per = ceil_div(blocks, want);          // blocks per part
+    const int64_t want = std::max<int64_t>(1, std::min<int64_t>(parts[i], blocks));
+    const int64_t per = std::max<int64_t>(1, ceil_div(blocks, want));   // blocks per part
     const int64_t nparts = ceil_div(blocks, per);        // parts that are not empty
-    if (nparts <= 1) {
+    if (nparts <= 1) {   // also an empty panel: one work item without bricks
       items.push_back(WorkItem{p, b0, b0 + (uint32_t)nbp, kNoSlot});
       wl->h_items.push_back(spmm_work_item_t{p, b0, b0 + (uint32_t)nbp, 0, 1});
       continue;
