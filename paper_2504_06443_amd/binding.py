@@ -121,7 +121,8 @@ class Plan:
 
     def destroy(self):
         if getattr(self, "_h", None):
-            _lib.spmm_plan_destroy(self._h)
+            if _lib is not None:          # (None while the interpreter shuts down)
+                _lib.spmm_plan_destroy(self._h)
             self._h = None
 
 
