@@ -90,18 +90,22 @@ def test_config4_fem(gpu):
         check_full(gpu, A, N, "config4", check_format=(N == Ns[0]))
 
 
-def test_b_larger_than_4gib_uses_64bit_offsets(gpu):
+@pytest.mark.parametrize("K,N", [(1 << 21, 520), ((1 << 20) - 1, 1024)],
+                         ids=["above_4gib", "just_below_4gib"])
+def test_b_around_4gib(gpu, K, N):
     """B of 4.4 GB: byte offsets into B no longer fit 32 bits, which must switch the
-    library to its 64-bit addressing kernel; rows at both ends of B are referenced."""
+    library to its 64-bit addressing kernel.  B of 4 GiB minus one row: the 32-bit
+    offsets of the fast kernel come within 4 KB of wrapping.  Rows at both ends of B
+    are referenced."""
     import torch
-    K, N, M = 1 << 21, 520, 4096
+    M = 4096
     rng = np.random.default_rng(7)
     per_row = 24
     rows = np.repeat(np.arange(M), per_row)
     cols = np.concatenate([rng.integers(0, K, size=M * per_row - 64),
                            np.arange(K - 32, K), np.arange(0, 32)])
     A = W.csr_from_coo(M, K, rows, cols, rng.uniform(-1, 1, size=rows.size).astype(np.float32))
-    assert 4 * K * N >= 1 << 32
+    assert (4 * K * N >= 1 << 32) == (N == 520)
     gen = torch.Generator(device="cuda").manual_seed(11)
     Bd = torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32)
     plan = make_plan(gpu, A)
