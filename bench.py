@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--n", type=int, default=0, help="columns of B (default: the workload's)")
     ap.add_argument("--route", default="auto", choices=["auto", "mfma", "valu", "class"])
     ap.add_argument("--split", type=int, default=0)
+    ap.add_argument("--order", default="panel", choices=["panel", "heavy"],
+                    help="work-item order: panel order, or heaviest first (the schedule the paper rejects)")
     ap.add_argument("--cold", action="store_true",
                     help="rotate over several B/C pairs so that no step finds its operands in cache")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -137,6 +139,7 @@ def main():
 
     spmm.spmm_plan_set_route(plan, {"auto": 0, "mfma": 1, "valu": 2, "class": 3}[args.route])
     spmm.spmm_plan_set_split(plan, args.split)
+    spmm.spmm_plan_set_order(plan, 1 if args.order == "heavy" else 0)
     syn = spmm.spmm_synergy(plan, N)
     wl = spmm.spmm_plan_worklist(plan, N)
 
@@ -208,7 +211,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "M": A.M, "K": A.K, "nnz": A.nnz, "N": N,
-                   "route": args.route, "cold": bool(args.cold), "bc_pairs": n_pairs},
+                   "route": args.route, "order": args.order, "cold": bool(args.cold), "bc_pairs": n_pairs},
         "kernel_ms_mean": kernel_ms,
         "kernel_ms_median": kernel_ms_med,
         "plan_ms": plan_ms,

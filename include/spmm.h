@@ -175,6 +175,13 @@ int spmm_plan_export(const spmm_plan_t *plan, uint32_t *panel_ptr /* host [P+1] 
 int spmm_plan_set_route(spmm_plan_t *plan, int route);
 int spmm_plan_set_split(spmm_plan_t *plan, int parts);
 
+/* Order in which the work items of the MFMA kernel are handed to the wavefronts.  Section 5
+ * considers and rejects sorting panels by weight, because consecutive panels share B rows;
+ * SPMM_ORDER_HEAVY_FIRST is that rejected schedule, kept to measure the argument
+ * (heaviest work item first, ties in panel order).  Drops cached work lists. */
+enum spmm_order { SPMM_ORDER_PANEL = 0, SPMM_ORDER_HEAVY_FIRST = 1 };
+int spmm_plan_set_order(spmm_plan_t *plan, int order);
+
 /* Host-only arithmetic of Eq. 6-7; needs no GPU.
  *   n_panels, nbricks[n_panels]  bricks per panel (a block is 4 bricks)
  *   work_items   thread-block count before splitting ("Total_thread_blocks")

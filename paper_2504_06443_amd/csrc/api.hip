@@ -84,6 +84,7 @@ struct spmm_plan {
   int64_t n_active_cols = 0;
   int route = SPMM_ROUTE_AUTO;
   int split = 0;
+  int order = SPMM_ORDER_PANEL;
   std::map<int64_t, WorkList*> lists;
 
   void drop_lists() {
@@ -226,6 +227,23 @@ int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** ou
           spmm_work_item_t{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)q, (uint32_t)nparts});
     }
     slots += nparts;
+  }
+  if (pl->order == SPMM_ORDER_HEAVY_FIRST) {
+    // the schedule Section 5 argues against (it gives up the locality of consecutive panels);
+    // kept as an experiment
+    std::vector<size_t> perm(items.size());
+    for (size_t i = 0; i < perm.size(); ++i) perm[i] = i;
+    std::stable_sort(perm.begin(), perm.end(), [&](size_t l, size_t r) {
+      return items[l].brick_end - items[l].brick_begin > items[r].brick_end - items[r].brick_begin;
+    });
+    std::vector<WorkItem> sorted_items(items.size());
+    std::vector<spmm_work_item_t> sorted_h(items.size());
+    for (size_t i = 0; i < perm.size(); ++i) {
+      sorted_items[i] = items[perm[i]];
+      sorted_h[i] = wl->h_items[perm[i]];
+    }
+    items.swap(sorted_items);
+    wl->h_items.swap(sorted_h);
   }
   wl->info.n_mfma_items = (int64_t)items.size();
   wl->info.n_valu_panels = (int64_t)wl->h_valu_panels.size();
@@ -617,6 +635,16 @@ int spmm_plan_set_split(spmm_plan_t* pl, int parts) {
   if (parts < 0) return fail(SPMM_EINVAL, "parts is negative");
   if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
   pl->split = parts;
+  pl->drop_lists();
+  return SPMM_OK;
+}
+
+int spmm_plan_set_order(spmm_plan_t* pl, int order) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (order != SPMM_ORDER_PANEL && order != SPMM_ORDER_HEAVY_FIRST)
+    return fail(SPMM_EINVAL, "unknown order");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
+  pl->order = order;
   pl->drop_lists();
   return SPMM_OK;
 }

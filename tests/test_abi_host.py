@@ -77,6 +77,7 @@ def test_null_plan_is_an_error_not_a_crash(binding):
     assert binding._lib.spmm_synergy(None, 4, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_plan_sizes(None, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_plan_update_values(None, None, None) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_plan_set_order(None, 0) == binding.SPMM_EINVAL
     binding._lib.spmm_plan_destroy(None)
     out = ctypes.c_void_p()
     assert binding._lib.spmm_plan(-1, 1, 0, None, None, None, None, ctypes.byref(out)) == binding.SPMM_EINVAL

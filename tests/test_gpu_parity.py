@@ -451,3 +451,22 @@ def test_plans_release_their_memory(gpu):
     torch.cuda.empty_cache()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < 8 << 20, f"device memory shrank by {(free0 - free1) >> 20} MiB over 90 plans"
+
+
+def test_heavy_first_order_gives_the_same_product(gpu):
+    """The sorted schedule that Section 5 discusses and rejects: same product bit for bit
+    (each work item computes the same tile; only the dispatch order changes), work items
+    in descending size."""
+    A = W.power_law(M=3000, target_nnz=None, cap=900, alpha=1.7, seed=61)
+    B = W.dense_b(A.K, 96, 62)
+    Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+    plan = make_plan(gpu, A)
+    C_panel = run_product(gpu, plan, A, B, route=gpu.ROUTE_MFMA)
+    gpu.spmm_plan_set_order(plan, gpu.ORDER_HEAVY_FIRST)
+    C_heavy = run_product(gpu, plan, A, B, route=gpu.ROUTE_MFMA)
+    check_c(C_heavy, Cref, S)
+    assert np.array_equal(C_panel, C_heavy)
+    sizes = [int(b1) - int(b0) for _, b0, b1, _, _ in gpu.spmm_plan_worklist(plan, 96)["items"]]
+    assert sizes == sorted(sizes, reverse=True) and len(set(sizes)) > 3
+    with pytest.raises(gpu.SpmmError):
+        gpu.spmm_plan_set_order(plan, 5)
