@@ -404,7 +404,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
     HIP_TRY(launch_panel_sort_census(rowptr, colind, M, K, P, sort_cap, d_err, nbricks_p,
                                      panel_nnzptr, ncols_p, pl->ent_pos, d_active, d_maxnb, s));
   } else {
-    // ---- search-based path for matrices with a panel wider than the LDS bitmap.  Its a1
+    // ---- search-based path for every other matrix.  Its a1
     // kernels only compare columns, so they may run before the host has seen the verdict of
     // the column check; everything that indexes by column or rank runs after it.
     status = wide_a1();
