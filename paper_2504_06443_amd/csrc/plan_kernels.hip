@@ -511,33 +511,45 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_census(
 // Equal columns end up next to each other: flags + a scan give the rank of every column, with
 // no dependence on the width of the panel's column span.
 // Loads the keys (padded with all-ones to n_sort, a power of two >= 64), checks the columns,
-// sorts ascending.
+// sorts ascending.  KT = uint32_t packs (column << 11 | index) for matrices with fewer than
+// 2^21 columns and panels of at most 2048 entries: half the LDS traffic of 64-bit keys.
+template <typename KT> struct SortKey;
+template <> struct SortKey<unsigned long long> {
+  static __device__ unsigned long long make(uint32_t col, uint32_t idx) { return ((unsigned long long)col << 32) | idx; }
+  static __device__ uint32_t col(unsigned long long k) { return (uint32_t)(k >> 32); }
+  static __device__ uint32_t idx(unsigned long long k) { return (uint32_t)k; }
+};
+template <> struct SortKey<uint32_t> {
+  static __device__ uint32_t make(uint32_t col, uint32_t idx) { return (col << 11) | idx; }
+  static __device__ uint32_t col(uint32_t k) { return k >> 11; }
+  static __device__ uint32_t idx(uint32_t k) { return k & 2047u; }
+};
+
+template <typename KT>
 __device__ inline void panel_sort(const int32_t* __restrict__ colind, const PanelExtent& x,
-                                  const int32_t* rp, int64_t K, uint32_t n_sort,
-                                  unsigned long long* keys, uint32_t* err) {
+                                  const int32_t* rp, int64_t K, uint32_t n_sort, KT* keys,
+                                  uint32_t* err) {
   const uint32_t n = (uint32_t)(x.e1 - x.e0);
   uint32_t bad = 0;
   for (uint32_t i = threadIdx.x; i < n_sort; i += kPanelThreads) {
-    unsigned long long key = ~0ull;
+    KT key = (KT)~(KT)0;
     if (i < n) {
       const int64_t e = x.e0 + i;
       const int32_t j = colind[e];
-      if (err) {
-        if (j < 0 || j >= K) bad |= kErrColRange;
-        if (e > rp[row_in_panel(rp, e)] && colind[e - 1] >= j) bad |= kErrColOrder;
-      }
-      key = ((unsigned long long)(uint32_t)j << 32) | i;
+      if (j < 0 || j >= K) bad |= kErrColRange;
+      if (e > rp[row_in_panel(rp, e)] && colind[e - 1] >= j) bad |= kErrColOrder;
+      key = SortKey<KT>::make((uint32_t)j, i);
     }
     keys[i] = key;
   }
-  if (err && bad) atomicOr(err, bad);
+  if (bad) atomicOr(err, bad);
   __syncthreads();
   for (uint32_t k = 2; k <= n_sort; k <<= 1) {
     for (uint32_t j = k >> 1; j > 0; j >>= 1) {
       for (uint32_t i = threadIdx.x; i < n_sort / 2; i += kPanelThreads) {
         const uint32_t a = ((i & ~(j - 1)) << 1) | (i & (j - 1));
         const uint32_t b = a | j;
-        const unsigned long long ka = keys[a], kb = keys[b];
+        const KT ka = keys[a], kb = keys[b];
         const bool ascending = (a & k) == 0;
         if ((ka > kb) == ascending) { keys[a] = kb; keys[b] = ka; }
       }
@@ -554,12 +566,14 @@ __device__ inline uint32_t sort_size(uint32_t n) {
 
 // census by sorting: distinct columns of each panel; validates colind; leaves the sorted order
 // of each panel's entries (indices inside the panel) in `order`.  Dynamic LDS: keys.
+template <typename KT>
 __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_census(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind, int64_t M, int64_t K,
     int64_t P, uint32_t n_cap, uint32_t* err, uint32_t* __restrict__ nbricks_p,
     uint32_t* __restrict__ panel_nnzptr, uint32_t* __restrict__ ncols_p,
     uint32_t* __restrict__ order) {
   extern __shared__ unsigned long long lds64[];
+  KT* keys = reinterpret_cast<KT*>(lds64);
   __shared__ int32_t rp[kPanel + 1];
   if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;   // uniform: nothing below is safe
   const int64_t p = blockIdx.x;
@@ -573,11 +587,11 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_sort_census(
     if (threadIdx.x == 0) { nbricks_p[p] = 0; ncols_p[p] = 0; }
     return;
   }
-  panel_sort(colind, x, rp, K, sort_size(n), lds64, err);
+  panel_sort<KT>(colind, x, rp, K, sort_size(n), keys, err);
   uint32_t cnt = 0;
   for (uint32_t i = threadIdx.x; i < n; i += kPanelThreads) {
-    cnt += (i == 0 || (uint32_t)(lds64[i] >> 32) != (uint32_t)(lds64[i - 1] >> 32)) ? 1u : 0u;
-    order[x.e0 + i] = (uint32_t)lds64[i];   // sorted order of the panel's entries, for the build
+    cnt += (i == 0 || SortKey<KT>::col(keys[i]) != SortKey<KT>::col(keys[i - 1])) ? 1u : 0u;
+    order[x.e0 + i] = SortKey<KT>::idx(keys[i]);   // sorted order of the panel's entries
   }
   uint32_t total;
   wave_exclusive(cnt, &total);
@@ -973,14 +987,23 @@ hipError_t launch_panel_sort_census(const int32_t* rowptr, const int32_t* colind
                                     uint32_t* order, unsigned long long* n_active,
                                     uint32_t* max_cols, hipStream_t s) {
   if (P == 0) return hipSuccess;
-  const size_t lds = (size_t)n_cap * 8;
+  const bool narrow = K < (int64_t(1) << 21) && n_cap <= 2048;   // (column, index) fits 32 bits
+  const size_t lds = (size_t)n_cap * (narrow ? 4 : 8);
+  const void* fn = narrow ? reinterpret_cast<const void*>(k_panel_sort_census<uint32_t>)
+                          : reinterpret_cast<const void*>(k_panel_sort_census<unsigned long long>);
   if (lds > 48 * 1024) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_panel_sort_census),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const hipError_t e =
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k_panel_sort_census, dim3((unsigned)P), dim3(kPanelThreads), lds, s, rowptr,
-                     colind, M, K, P, n_cap, err, nbricks_p, panel_nnzptr, ncols_p, order);
+  if (narrow)
+    hipLaunchKernelGGL(k_panel_sort_census<uint32_t>, dim3((unsigned)P), dim3(kPanelThreads), lds,
+                       s, rowptr, colind, M, K, P, n_cap, err, nbricks_p, panel_nnzptr, ncols_p,
+                       order);
+  else
+    hipLaunchKernelGGL(k_panel_sort_census<unsigned long long>, dim3((unsigned)P),
+                       dim3(kPanelThreads), lds, s, rowptr, colind, M, K, P, n_cap, err, nbricks_p,
+                       panel_nnzptr, ncols_p, order);
   hipLaunchKernelGGL(k_cols_sum_max, dim3((unsigned)std::min<int64_t>(grid_for(P), 1024)),
                      dim3(kThreads), 0, s, ncols_p, P, n_active, max_cols);
   return hipGetLastError();

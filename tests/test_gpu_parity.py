@@ -380,7 +380,8 @@ def test_plan_paths_for_wide_panels(gpu):
              "scattered_cost_rule": scattered(700_000, 70, 900),       # sorted per panel
              "large_lds": shared_columns(700_000, 300),                # bitmap, large LDS
              "late_fallback": shared_columns(700_000, 2400),           # bitmap, then searches
-             "search_path": shared_columns(1_300_000, 600)}            # searches from the start
+             "search_path": shared_columns(1_300_000, 600),            # searches from the start
+             "sort_wide_keys": scattered(3_000_000, 70, 900)}          # sorted, 64-bit keys
     for name, A in cases.items():
         print(f"wide panel case {name}: K={A.K} nnz={A.nnz}", flush=True)
         plan = make_plan(gpu, A)
