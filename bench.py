@@ -101,6 +101,9 @@ def main():
     import numpy as np
     import torch
 
+    if not os.path.exists(os.path.join(ROOT, "paper_2504_06443_amd", "libspmm_brick.so")):
+        from paper_2504_06443_amd.build import build_library   # nothing built yet: build once
+        build_library(verbose=False)
     from paper_2504_06443_amd import binding as spmm
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
