@@ -159,17 +159,23 @@ def _ceil_div(a: int, b: int) -> int:
 
 
 def partition_counts(nbricks_per_panel, total_work_items: int, num_cus: int,
-                     resident_per_cu: int):
+                     resident_per_cu: int, policy: str = "from2"):
     """Number of virtual panels each row panel is split into.
 
     blocks_p = ceil(bricks_p / 4) (a block is TK/brick_k = 4 brick columns);
     num_waves = ceil(total_work_items / (num_cus * resident_per_cu)), at least 1;
     num_loads_p = blocks_p / average blocks over all panels (Eq. 6);
-    partition_ratio_p = num_loads_p / num_waves (Eq. 7);
-    parts_p = 1 if partition_ratio_p < 2, else round-half-up(partition_ratio_p),
-    evaluated in integers (the paper gives no rounding rule: a ratio of exactly 1
-    must not split; a panel is split once it carries two wave-adjusted average loads).
+    partition_ratio_p = num_loads_p / num_waves (Eq. 7).
+    The paper gives no rounding rule beyond "no partition if the ratio is 1".  Two readings,
+    both evaluated in integers:
+      "nearest"  parts_p = max(1, round-half-up(partition_ratio_p)): the literal one, a
+                 panel is split once its ratio reaches 1.5;
+      "from2"    parts_p = 1 while partition_ratio_p < 2, else round-half-up: a panel is
+                 split once it carries two wave-adjusted average loads (the default of
+                 the library, chosen there by measurement).
     Returns (parts list, num_waves)."""
+    if policy not in ("from2", "nearest"):
+        raise ValueError("policy must be 'from2' or 'nearest'")
     blocks = [_ceil_div(int(b), 4) for b in nbricks_per_panel]
     P = len(blocks)
     total = sum(blocks)
@@ -180,7 +186,10 @@ def partition_counts(nbricks_per_panel, total_work_items: int, num_cus: int,
             parts.append(1)
         else:
             num, den = b * P, total * waves          # partition_ratio = num / den
-            parts.append(1 if num < 2 * den else (2 * num + den) // (2 * den))
+            nearest = (2 * num + den) // (2 * den)
+            if policy == "from2" and num < 2 * den:
+                nearest = 1
+            parts.append(max(1, nearest))
     return parts, waves
 
 

@@ -109,6 +109,26 @@ def test_counts_against_independent_numpy():
     assert s["alpha_col"] >= s["alpha_brick"]        # padding only lowers the brick figure
 
 
+def test_bytes_model_hand_counted(golden_dir):
+    """bytes_min / bytes_noreuse and both HBM operational intensities against integers counted
+    by hand for a two-panel matrix (derivation in the golden file)."""
+    g = dict((k, int(v)) for k, v in read_rows(os.path.join(golden_dir, "bytes_model_example.txt")))
+    rows = [0, 3, 5, 16, 17, 18, 19, 20]
+    cols = [1, 1, 6, 1, 2, 3, 4, 5]
+    A = W.csr_from_coo(32, 8, rows, cols, np.ones(8, np.float32))
+    s, _ = synergy_of(A, N=4)
+    for k in ("nnz", "n_bricks", "n_active_cols", "n_distinct_cols"):
+        assert s[k] == g[k], k
+    assert s["bytes_min"] == g["bytes_min"] and s["bytes_noreuse"] == g["bytes_noreuse"]
+    assert s["oi_hbm_min"] == pytest.approx(g["flops"] / g["bytes_min"], rel=1e-15)
+    assert s["oi_hbm_noreuse"] == pytest.approx(g["flops"] / g["bytes_noreuse"], rel=1e-15)
+    assert s["oi_hbm_noreuse"] < s["oi_hbm_min"]
+    # a matrix whose panels share no column has nothing to reuse: both models coincide
+    B = W.csr_from_coo(32, 8, [0, 1, 16, 17], [0, 1, 2, 3], np.ones(4, np.float32))
+    t, _ = synergy_of(B, N=4)
+    assert t["bytes_noreuse"] == t["bytes_min"] and t["oi_hbm_noreuse"] == t["oi_hbm_min"]
+
+
 def test_per_panel_classes_mixed():
     # panel 0: dense 16x4 (High); panel 1: one entry (Low); panel 2: empty; panel 3: 8 in a column (Medium)
     rows = list(np.repeat(np.arange(16), 4)) + [20] + list(48 + np.arange(8))
@@ -141,19 +161,60 @@ def test_uniform_panels_never_split():
         assert set(parts) == {1}
 
 
+def rounding_rows(golden_dir):
+    out = []
+    for name, blocks, ratio, nearest, from2, others in read_rows(
+            os.path.join(golden_dir, "load_balance_rounding.txt")):
+        out.append((name, [int(b) for b in blocks.split(",")], Fraction(ratio), int(nearest),
+                    int(from2), int(others)))
+    return out
+
+
+def test_rounding_of_eq7_hand_worked(golden_dir):
+    """Both readings of Eq. 7's rounding against examples worked by hand (one wave of work)."""
+    rows = rounding_rows(golden_dir)
+    assert len(rows) >= 8
+    for name, blocks, ratio, nearest, from2, others in rows:
+        bricks = [4 * b for b in blocks]
+        P = len(blocks)
+        assert Fraction(blocks[0] * P, sum(blocks)) == ratio, name      # the fixture's own arithmetic
+        for policy, want in (("nearest", nearest), ("from2", from2)):
+            parts, waves = oracle.partition_counts(bricks, P, 1000, 1, policy=policy)
+            assert waves == 1
+            assert parts[0] == want, (name, policy)
+            assert set(parts[1:]) == {others}, (name, policy)
+
+
+def test_more_waves_divide_the_ratio():
+    """Eq. 7 divides the load by the number of waves: the panel of example a (ratio 32/3 in
+    one wave) gets round(32/3 / 2) = 5 parts with two waves of work, 32/9 -> 4 with three,
+    and 1 once the waves reach the ratio."""
+    bricks = [4 * 30] + [4] * 15
+    for items_per_capacity, want in ((1, 11), (2, 5), (3, 4), (8, 1), (11, 1)):
+        for policy in ("nearest", "from2"):
+            parts, waves = oracle.partition_counts(bricks, 16 * items_per_capacity, 16, 1, policy=policy)
+            assert waves == items_per_capacity
+            expect = want
+            if policy == "from2" and Fraction(32, 3) / items_per_capacity < 2:
+                expect = 1
+            assert parts[0] == expect, (items_per_capacity, policy)
+
+
 def test_split_follows_eq6_eq7_exact_fractions():
     bricks = [400, 8, 8, 8, 40, 0, 8, 8]
     P = len(bricks)
     for items, cus, res in ((8, 4, 1), (8, 2, 1), (64, 4, 2), (8, 256, 8)):
-        parts, waves = oracle.partition_counts(bricks, items, cus, res)
-        blocks = [Fraction(-(-b // 4)) for b in bricks]
-        avg = sum(blocks) / P
-        w = max(1, -(-items // (cus * res)))
-        assert waves == w
-        for p in range(P):
-            ratio = blocks[p] / avg / w                     # Eq. 6 then Eq. 7
-            expect = 1 if ratio < 2 else int((ratio + Fraction(1, 2)) // 1)   # nearest, halves up
-            assert parts[p] == expect
+        for policy in ("from2", "nearest"):
+            parts, waves = oracle.partition_counts(bricks, items, cus, res, policy=policy)
+            blocks = [Fraction(-(-b // 4)) for b in bricks]
+            avg = sum(blocks) / P
+            w = max(1, -(-items // (cus * res)))
+            assert waves == w
+            for p in range(P):
+                ratio = blocks[p] / avg / w                     # Eq. 6 then Eq. 7
+                nearest = max(1, int((ratio + Fraction(1, 2)) // 1))   # nearest, halves up
+                expect = 1 if (policy == "from2" and ratio < 2) else nearest
+                assert parts[p] == expect
 
 
 def test_ranges_tile_the_panel_once():
