@@ -161,17 +161,22 @@ int spmm_plan_export(const spmm_plan_t *plan, uint32_t *panel_ptr /* host [P+1] 
  * Routing and load balancing (Section 5).  Both setters drop cached work lists.
  *
  * spmm_plan_set_route: which kernel handles which panel (enum spmm_route).
- * spmm_plan_set_split: how heavy panels are split along K into virtual panels:
- *   parts = 0  Eq. 6-7: ratio_p = blocks_p / avg_blocks / num_waves; parts_p = 1 while
- *              ratio_p < 2, else round(ratio_p);
- *              num_waves = ceil(work items / (CUs * resident waves per CU))
- *   parts = 1  never split
- *   parts > 1  split every panel that has at least `parts` blocks into `parts`
- *              (for tests of the merge path)
+ * spmm_plan_set_split: how heavy panels are split along K into virtual panels
+ *   (Eq. 6-7: ratio_p = blocks_p / avg_blocks / num_waves, with
+ *   num_waves = ceil(work items / (CUs * resident waves per CU)); the paper gives no
+ *   rounding rule beyond "no partition if the ratio is 1"):
+ *   SPMM_SPLIT_EQ7_FROM2 (0)    parts_p = 1 while ratio_p < 2, else round-half-up(ratio_p);
+ *                               the default, chosen by measurement on MI355X
+ *   SPMM_SPLIT_EQ7_NEAREST (-1) parts_p = max(1, round-half-up(ratio_p)): the literal reading,
+ *                               a panel is split from ratio 1.5
+ *   1                           never split
+ *   parts > 1                   split every panel that has at least `parts` blocks into
+ *                               `parts` (for tests of the merge path)
  * Partial tiles of a split panel go to a plan-owned workspace and are summed in
  * part order by a merge kernel, so results stay deterministic (the paper merges
  * with atomics).
  */
+enum spmm_split_policy { SPMM_SPLIT_EQ7_NEAREST = -1, SPMM_SPLIT_EQ7_FROM2 = 0, SPMM_SPLIT_NEVER = 1 };
 int spmm_plan_set_route(spmm_plan_t *plan, int route);
 int spmm_plan_set_split(spmm_plan_t *plan, int parts);
 
@@ -186,11 +191,12 @@ int spmm_plan_set_order(spmm_plan_t *plan, int order);
  *   n_panels, nbricks[n_panels]  bricks per panel (a block is 4 bricks)
  *   work_items   thread-block count before splitting ("Total_thread_blocks")
  *   num_cus, resident_per_cu     device capacity for one wave of work
+ *   policy                       SPMM_SPLIT_EQ7_FROM2 or SPMM_SPLIT_EQ7_NEAREST
  *   parts_out[n_panels]          virtual panels per panel (>= 1)
  *   waves_out                    num_waves (may be NULL)
  */
 int spmm_partition_counts(int64_t n_panels, const uint32_t *nbricks /* host */, int64_t work_items,
-                          int32_t num_cus, int32_t resident_per_cu,
+                          int32_t num_cus, int32_t resident_per_cu, int32_t policy,
                           uint32_t *parts_out /* host */, int64_t *waves_out /* host */);
 
 /* Work list that spmm_exec would use for N (builds and caches it).
@@ -207,6 +213,10 @@ typedef struct spmm_worklist_info {
   int64_t num_waves;      /* Eq. 7 denominator actually used                  */
   int32_t n_tile;         /* columns of C per wavefront (16, 32, 64 or 128)   */
   int32_t n_tiles;        /* ceil(N / n_tile)                                 */
+  int32_t num_cus;        /* compute units of the plan's device               */
+  int32_t resident_waves_per_cu; /* wavefronts of the MFMA kernel variant for
+                             this N that fit on one CU at a time; num_waves =
+                             max(1, ceil(panels * n_tiles / (num_cus * this))) */
 } spmm_worklist_info_t;
 
 int spmm_plan_worklist(spmm_plan_t *plan, int64_t N, spmm_worklist_info_t *info /* host */,

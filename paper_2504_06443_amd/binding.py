@@ -27,10 +27,12 @@ _lib = C.CDLL(LIB_PATH)
 SPMM_OK, SPMM_EINVAL, SPMM_EFORMAT, SPMM_ENOMEM, SPMM_EHIP, SPMM_ELIMIT = 0, -1, -2, -3, -4, -5
 ROUTE_AUTO, ROUTE_MFMA, ROUTE_VALU, ROUTE_CLASS = 0, 1, 2, 3
 ORDER_PANEL, ORDER_HEAVY_FIRST = 0, 1
+SPLIT_EQ7_NEAREST, SPLIT_EQ7_FROM2, SPLIT_NEVER = -1, 0, 1
 CLASS_NAMES = ("Low", "Medium", "High")
 
 EXPORTED = (
-    "spmm_plan", "spmm_plan_update_values", "spmm_exec", "spmm_synergy", "spmm_plan_sizes",
+    "spmm_plan", "spmm_plan_update_values", "spmm_exec", "spmm_synergy",
+    "spmm_plan_sizes",
     "spmm_plan_export",
     "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_partition_counts",
     "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error",
@@ -71,7 +73,8 @@ class _WorkItem(C.Structure):
 class _WorklistInfo(C.Structure):
     _fields_ = [("n_mfma_items", C.c_int64), ("n_valu_panels", C.c_int64),
                 ("n_split_panels", C.c_int64), ("num_waves", C.c_int64),
-                ("n_tile", C.c_int32), ("n_tiles", C.c_int32)]
+                ("n_tile", C.c_int32), ("n_tiles", C.c_int32),
+                ("num_cus", C.c_int32), ("resident_waves_per_cu", C.c_int32)]
 
 
 _vp = C.c_void_p
@@ -85,8 +88,8 @@ _lib.spmm_plan_export.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.spmm_plan_set_route.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_split.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_order.argtypes = [_vp, C.c_int]
-_lib.spmm_partition_counts.argtypes = [C.c_int64, _vp, C.c_int64, C.c_int32, C.c_int32, _vp,
-                                       C.POINTER(C.c_int64)]
+_lib.spmm_partition_counts.argtypes = [C.c_int64, _vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                       _vp, C.POINTER(C.c_int64)]
 _lib.spmm_plan_worklist.argtypes = [_vp, C.c_int64, C.POINTER(_WorklistInfo), _vp, _vp]
 _lib.spmm_plan_destroy.argtypes = [_vp]
 _lib.spmm_plan_destroy.restype = None
@@ -131,6 +134,10 @@ class Plan:
 def spmm_plan(M: int, K: int, rowptr, colind, vals, stream=None) -> Plan:
     """CSR (device int32/int32/float32 tensors) -> plan holding the brick format."""
     nnz = int(colind.numel())
+    if int(rowptr.numel()) != M + 1:
+        raise ValueError("rowptr must have M + 1 entries")
+    if int(vals.numel()) != nnz:
+        raise ValueError("vals and colind must have the same length")
     out = _vp()
     _check(_lib.spmm_plan(M, K, nnz, _dev(rowptr, torch.int32),
                           _dev(colind, torch.int32) if nnz else None,
@@ -147,7 +154,7 @@ def spmm_plan_update_values(plan: Plan, vals, stream=None):
                                         _stream_ptr(stream)))
 
 
-def spmm_exec(plan: Plan, B, C_out=None, stream=None):
+def spmm_exec(plan: Plan, B, C_out=None, stream=None, _entry=None):
     """C = A . B on the current (or given) stream.  B: device float32 [K, N]."""
     N = int(B.shape[1])
     if B.shape[0] != plan.K:
@@ -156,9 +163,9 @@ def spmm_exec(plan: Plan, B, C_out=None, stream=None):
         C_out = torch.empty((plan.M, N), dtype=torch.float32, device=B.device)
     elif tuple(C_out.shape) != (plan.M, N):
         raise ValueError("C has the wrong shape")
-    _check(_lib.spmm_exec(plan._h, _dev(B, torch.float32) if B.numel() else None, N,
-                          _dev(C_out, torch.float32) if C_out.numel() else None,
-                          _stream_ptr(stream)))
+    entry = _entry or _lib.spmm_exec
+    _check(entry(plan._h, _dev(B, torch.float32) if B.numel() else None, N,
+                 _dev(C_out, torch.float32) if C_out.numel() else None, _stream_ptr(stream)))
     return C_out
 
 
@@ -209,13 +216,15 @@ def spmm_plan_set_order(plan: Plan, order: int):
     _check(_lib.spmm_plan_set_order(plan._h, order))
 
 
-def spmm_partition_counts(nbricks, work_items: int, num_cus: int, resident_per_cu: int):
+def spmm_partition_counts(nbricks, work_items: int, num_cus: int, resident_per_cu: int,
+                          policy: int = SPLIT_EQ7_FROM2):
     """Eq. 6-7 on the host (no GPU needed). Returns (parts per panel, num_waves)."""
     nb = np.ascontiguousarray(nbricks, dtype=np.uint32)
     parts = np.zeros(len(nb), dtype=np.uint32)
     waves = C.c_int64(0)
     _check(_lib.spmm_partition_counts(len(nb), nb.ctypes.data_as(_vp), work_items, num_cus,
-                                      resident_per_cu, parts.ctypes.data_as(_vp), C.byref(waves)))
+                                      resident_per_cu, policy, parts.ctypes.data_as(_vp),
+                                      C.byref(waves)))
     return parts, waves.value
 
 

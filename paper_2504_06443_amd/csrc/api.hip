@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <map>
 #include <new>
 #include <vector>
@@ -40,16 +41,24 @@ int fail(int code, const char* fmt, ...) {
 constexpr double kHbmBytesPerS = 8.0e12;    // MI355X published HBM3E bandwidth
 constexpr double kMfmaFp32Flops = 157.3e12; // MI355X published dense fp32 matrix peak
 
-struct WorkList {
+// Host half of a work list: what the routing and Eq. 6-7 decide for one N.
+struct HostList {
+  uint64_t id = 0;                          // unique per list (tags the contents of the static scratch)
   int64_t N = 0;
   spmm_worklist_info_t info{};
   std::vector<spmm_work_item_t> h_items;   // exported form
-  std::vector<uint32_t> h_valu_panels;
+  std::vector<WorkItem> items;             // device form
+  std::vector<MergeItem> merges;
+  std::vector<uint32_t> valu_panels;
+  int64_t n_slots = 0;                      // partial 16 x N tiles of split panels
+};
+
+// Device half: plan-owned copies of a HostList plus the partial-tile workspace.
+struct WorkList {
+  const HostList* host = nullptr;
   WorkItem* d_items = nullptr;
   uint32_t* d_valu_panels = nullptr;
   MergeItem* d_merge = nullptr;
-  int64_t n_merge = 0;
-  int64_t n_slots = 0;
   float* d_partial = nullptr;               // n_slots tiles of 16 x N
   ~WorkList() {
     if (d_items) (void)hipFree(d_items);
@@ -58,6 +67,8 @@ struct WorkList {
     if (d_partial) (void)hipFree(d_partial);
   }
 };
+
+std::atomic<uint64_t> g_next_list_id{1};
 
 }  // namespace
 
@@ -85,11 +96,14 @@ struct spmm_plan {
   int route = SPMM_ROUTE_AUTO;
   int split = 0;
   int order = SPMM_ORDER_PANEL;
+  std::map<int64_t, HostList*> host_lists;
   std::map<int64_t, WorkList*> lists;
 
   void drop_lists() {
     for (auto& kv : lists) delete kv.second;
     lists.clear();
+    for (auto& kv : host_lists) delete kv.second;
+    host_lists.clear();
   }
   // the arrays above are carved out of two device allocations
   char* fixed_arena = nullptr;   // panel_ptr, rowptr, colind, csr_vals, ent_pos
@@ -129,10 +143,12 @@ int classify(int64_t nnz, int64_t nb) {
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Eq. 6-7 in integers: partition_ratio_p = blocks_p * P / (total_blocks * waves); a panel is
-// split once the ratio reaches 2, into round-half-up(ratio) parts.
+// Eq. 6-7 in integers: partition_ratio_p = blocks_p * P / (total_blocks * waves).
+// SPMM_SPLIT_EQ7_FROM2 (the default): one part while the ratio is below 2, else the ratio
+// rounded to the nearest integer, halves up.  SPMM_SPLIT_EQ7_NEAREST: the ratio rounded to
+// the nearest integer from the start (a panel is split from ratio 1.5), at least one part.
 void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, int64_t capacity,
-                      uint32_t* parts, int64_t* waves_out) {
+                      int policy, uint32_t* parts, int64_t* waves_out) {
   int64_t total = 0;
   for (int64_t p = 0; p < P; ++p) total += ceil_div(nbricks[p], kBrickK);
   const int64_t waves = std::max<int64_t>(1, ceil_div(work_items, std::max<int64_t>(1, capacity)));
@@ -143,135 +159,164 @@ void partition_counts(int64_t P, const uint32_t* nbricks, int64_t work_items, in
       // blocks * P can exceed 2^63 only for absurd sizes; use 128-bit to be safe
       const __int128 num = (__int128)blocks * P;
       const __int128 den = (__int128)total * waves;
-      q = num < 2 * den ? 1 : (int64_t)((2 * num + den) / (2 * den));
+      const int64_t nearest = (int64_t)((2 * num + den) / (2 * den));
+      q = (policy == SPMM_SPLIT_EQ7_FROM2 && num < 2 * den) ? 1 : nearest;
     }
     parts[p] = (uint32_t)std::max<int64_t>(1, q);
   }
   if (waves_out) *waves_out = waves;
 }
 
-// Builds (and uploads) the work list for N.  Synchronises the stream once.
+// Routing and load balancing for N (host only, no device memory).  Cached in the plan.
+int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
+  auto found = pl->host_lists.find(N);
+  if (found != pl->host_lists.end()) {
+    *out = found->second;
+    return SPMM_OK;
+  }
+  HostList* hl = nullptr;
+  try {
+    hl = new HostList();
+    hl->id = g_next_list_id.fetch_add(1);
+    hl->N = N;
+    const int tile = mfma_tile_for(std::max<int64_t>(N, 1));
+    hl->info.n_tile = tile;
+    hl->info.n_tiles = (int32_t)ceil_div(std::max<int64_t>(N, 1), tile);
+    hl->info.num_cus = pl->num_cus;
+
+    // routing: which panels go to the MFMA kernel
+    std::vector<uint32_t> mfma_panels;
+    std::vector<uint32_t> nbricks;
+    for (int64_t p = 0; p < pl->P; ++p) {
+      const uint8_t cls = pl->h_panel_class[p];
+      bool to_mfma;
+      // an empty panel only needs its rows of C zeroed; either kernel does that, so it goes
+      // where the other panels go and does not cost a second launch
+      if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_AUTO || pl->route == SPMM_ROUTE_MFMA;
+      else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
+      else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
+      else if (pl->route == SPMM_ROUTE_CLASS) to_mfma = cls != SPMM_LOW;
+      else to_mfma = true;  // AUTO: the brick kernel is the faster one for every class on MI355X
+      if (to_mfma) {
+        mfma_panels.push_back((uint32_t)p);
+        nbricks.push_back(pl->h_panel_ptr[p + 1] - pl->h_panel_ptr[p]);
+      } else {
+        hl->valu_panels.push_back((uint32_t)p);
+      }
+    }
+
+    // load balancing over the MFMA panels
+    const int64_t nm = (int64_t)mfma_panels.size();
+    std::vector<uint32_t> parts((size_t)nm, 1u);
+    int64_t waves = 1;
+    const int resident = mfma_resident_waves_per_cu(std::max<int64_t>(N, 1), pl->K);
+    hl->info.resident_waves_per_cu = resident;
+    if (nm > 0) {
+      if (pl->split == SPMM_SPLIT_EQ7_FROM2 || pl->split == SPMM_SPLIT_EQ7_NEAREST) {
+        partition_counts(nm, nbricks.data(), nm * hl->info.n_tiles,
+                         (int64_t)pl->num_cus * resident, pl->split, parts.data(), &waves);
+      } else if (pl->split > 1) {
+        for (int64_t i = 0; i < nm; ++i)
+          if (ceil_div(nbricks[i], kBrickK) >= pl->split) parts[i] = (uint32_t)pl->split;
+      }
+    }
+    hl->info.num_waves = waves;
+
+    int64_t slots = 0;
+    for (int64_t i = 0; i < nm; ++i) {
+      const uint32_t p = mfma_panels[i];
+      const uint32_t b0 = pl->h_panel_ptr[p];
+      const int64_t nbp = nbricks[i];
+      const int64_t blocks = ceil_div(nbp, kBrickK);
+      const int64_t want = std::max<int64_t>(1, std::min<int64_t>(parts[i], blocks));
+      const int64_t per = std::max<int64_t>(1, ceil_div(blocks, want));   // blocks per part
+      const int64_t nparts = ceil_div(blocks, per);        // parts that are not empty
+      if (nparts <= 1) {   // also an empty panel: one work item without bricks
+        hl->items.push_back(WorkItem{p, b0, b0 + (uint32_t)nbp, kNoSlot});
+        hl->h_items.push_back(spmm_work_item_t{p, b0, b0 + (uint32_t)nbp, 0, 1});
+        continue;
+      }
+      hl->merges.push_back(MergeItem{p, (uint32_t)slots, (uint32_t)nparts});
+      for (int64_t q = 0; q < nparts; ++q) {
+        const int64_t lo = std::min<int64_t>(nbp, q * per * kBrickK);
+        const int64_t hi = std::min<int64_t>(nbp, (q + 1) * per * kBrickK);
+        hl->items.push_back(
+            WorkItem{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)(slots + q)});
+        hl->h_items.push_back(
+            spmm_work_item_t{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)q, (uint32_t)nparts});
+      }
+      slots += nparts;
+    }
+    if (pl->order == SPMM_ORDER_HEAVY_FIRST) {
+      // the schedule Section 5 argues against (it gives up the locality of consecutive panels);
+      // kept as an experiment
+      std::vector<size_t> perm(hl->items.size());
+      for (size_t i = 0; i < perm.size(); ++i) perm[i] = i;
+      std::stable_sort(perm.begin(), perm.end(), [&](size_t l, size_t r) {
+        return hl->items[l].brick_end - hl->items[l].brick_begin >
+               hl->items[r].brick_end - hl->items[r].brick_begin;
+      });
+      std::vector<WorkItem> sorted_items(hl->items.size());
+      std::vector<spmm_work_item_t> sorted_h(hl->items.size());
+      for (size_t i = 0; i < perm.size(); ++i) {
+        sorted_items[i] = hl->items[perm[i]];
+        sorted_h[i] = hl->h_items[perm[i]];
+      }
+      hl->items.swap(sorted_items);
+      hl->h_items.swap(sorted_h);
+    }
+    hl->info.n_mfma_items = (int64_t)hl->items.size();
+    hl->info.n_valu_panels = (int64_t)hl->valu_panels.size();
+    hl->info.n_split_panels = (int64_t)hl->merges.size();
+    hl->n_slots = slots;
+    pl->host_lists[N] = hl;
+  } catch (const std::bad_alloc&) {
+    delete hl;
+    return fail(SPMM_ENOMEM, "host allocation failed while building the work list");
+  }
+  *out = hl;
+  return SPMM_OK;
+}
+
+// Device copy of the work list for N (allocates; synchronises the stream once).
 int build_worklist(spmm_plan_t* pl, int64_t N, hipStream_t stream, WorkList** out) {
   auto found = pl->lists.find(N);
   if (found != pl->lists.end()) {
     *out = found->second;
     return SPMM_OK;
   }
-  int status = SPMM_OK;
+  const HostList* hl = nullptr;
+  int status = build_host_list(pl, N, &hl);
+  if (status != SPMM_OK) return status;
   WorkList* wl = new (std::nothrow) WorkList();
   if (!wl) return fail(SPMM_ENOMEM, "host allocation failed");
-  wl->N = N;
-  const int tile = mfma_tile_for(std::max<int64_t>(N, 1));
-  wl->info.n_tile = tile;
-  wl->info.n_tiles = (int32_t)ceil_div(std::max<int64_t>(N, 1), tile);
-
-  // routing: which panels go to the MFMA kernel
-  std::vector<uint32_t> mfma_panels;
-  std::vector<uint32_t> nbricks;
-  for (int64_t p = 0; p < pl->P; ++p) {
-    const uint8_t cls = pl->h_panel_class[p];
-    bool to_mfma;
-    // an empty panel only needs its rows of C zeroed; either kernel does that, so it goes
-    // where the other panels go and does not cost a second launch
-    if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_AUTO || pl->route == SPMM_ROUTE_MFMA;
-    else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
-    else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
-    else if (pl->route == SPMM_ROUTE_CLASS) to_mfma = cls != SPMM_LOW;
-    else to_mfma = true;  // AUTO: the brick kernel is the faster one for every class on MI355X
-    if (to_mfma) {
-      mfma_panels.push_back((uint32_t)p);
-      nbricks.push_back(pl->h_panel_ptr[p + 1] - pl->h_panel_ptr[p]);
-    } else {
-      wl->h_valu_panels.push_back((uint32_t)p);
-    }
-  }
-
-  // load balancing over the MFMA panels
-  const int64_t nm = (int64_t)mfma_panels.size();
-  std::vector<uint32_t> parts((size_t)nm, 1u);
-  int64_t waves = 1;
-  if (nm > 0) {
-    if (pl->split == 0) {
-      const int resident = mfma_resident_waves_per_cu(std::max<int64_t>(N, 1), pl->K);
-      partition_counts(nm, nbricks.data(), nm * wl->info.n_tiles,
-                       (int64_t)pl->num_cus * resident, parts.data(), &waves);
-    } else if (pl->split > 1) {
-      for (int64_t i = 0; i < nm; ++i)
-        if (ceil_div(nbricks[i], kBrickK) >= pl->split) parts[i] = (uint32_t)pl->split;
-    }
-  }
-  wl->info.num_waves = waves;
-
-  std::vector<WorkItem> items;
-  std::vector<MergeItem> merges;
-  int64_t slots = 0;
-  for (int64_t i = 0; i < nm; ++i) {
-    const uint32_t p = mfma_panels[i];
-    const uint32_t b0 = pl->h_panel_ptr[p];
-    const int64_t nbp = nbricks[i];
-    const int64_t blocks = ceil_div(nbp, kBrickK);
-    const int64_t want = std::max<int64_t>(1, std::min<int64_t>(parts[i], blocks));
-    const int64_t per = std::max<int64_t>(1, ceil_div(blocks, want));   // blocks per part
-    const int64_t nparts = ceil_div(blocks, per);        // parts that are not empty
-    if (nparts <= 1) {   // also an empty panel: one work item without bricks
-      items.push_back(WorkItem{p, b0, b0 + (uint32_t)nbp, kNoSlot});
-      wl->h_items.push_back(spmm_work_item_t{p, b0, b0 + (uint32_t)nbp, 0, 1});
-      continue;
-    }
-    merges.push_back(MergeItem{p, (uint32_t)slots, (uint32_t)nparts});
-    for (int64_t q = 0; q < nparts; ++q) {
-      const int64_t lo = std::min<int64_t>(nbp, q * per * kBrickK);
-      const int64_t hi = std::min<int64_t>(nbp, (q + 1) * per * kBrickK);
-      items.push_back(WorkItem{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)(slots + q)});
-      wl->h_items.push_back(
-          spmm_work_item_t{p, b0 + (uint32_t)lo, b0 + (uint32_t)hi, (uint32_t)q, (uint32_t)nparts});
-    }
-    slots += nparts;
-  }
-  if (pl->order == SPMM_ORDER_HEAVY_FIRST) {
-    // the schedule Section 5 argues against (it gives up the locality of consecutive panels);
-    // kept as an experiment
-    std::vector<size_t> perm(items.size());
-    for (size_t i = 0; i < perm.size(); ++i) perm[i] = i;
-    std::stable_sort(perm.begin(), perm.end(), [&](size_t l, size_t r) {
-      return items[l].brick_end - items[l].brick_begin > items[r].brick_end - items[r].brick_begin;
-    });
-    std::vector<WorkItem> sorted_items(items.size());
-    std::vector<spmm_work_item_t> sorted_h(items.size());
-    for (size_t i = 0; i < perm.size(); ++i) {
-      sorted_items[i] = items[perm[i]];
-      sorted_h[i] = wl->h_items[perm[i]];
-    }
-    items.swap(sorted_items);
-    wl->h_items.swap(sorted_h);
-  }
-  wl->info.n_mfma_items = (int64_t)items.size();
-  wl->info.n_valu_panels = (int64_t)wl->h_valu_panels.size();
-  wl->info.n_split_panels = (int64_t)merges.size();
-  wl->n_merge = (int64_t)merges.size();
-  wl->n_slots = slots;
-
-  HIP_TRY(dev_alloc(&wl->d_items, (int64_t)items.size()));
-  HIP_TRY(dev_alloc(&wl->d_valu_panels, (int64_t)wl->h_valu_panels.size()));
-  HIP_TRY(dev_alloc(&wl->d_merge, (int64_t)merges.size()));
-  if (slots > 0) HIP_TRY(dev_alloc(&wl->d_partial, slots * kPanel * std::max<int64_t>(N, 1)));
-  if (!items.empty())
-    HIP_TRY(hipMemcpyAsync(wl->d_items, items.data(), items.size() * sizeof(WorkItem),
+  wl->host = hl;
+  HIP_TRY(dev_alloc(&wl->d_items, (int64_t)hl->items.size()));
+  HIP_TRY(dev_alloc(&wl->d_valu_panels, (int64_t)hl->valu_panels.size()));
+  HIP_TRY(dev_alloc(&wl->d_merge, (int64_t)hl->merges.size()));
+  if (hl->n_slots > 0)
+    HIP_TRY(dev_alloc(&wl->d_partial, hl->n_slots * kPanel * std::max<int64_t>(N, 1)));
+  if (!hl->items.empty())
+    HIP_TRY(hipMemcpyAsync(wl->d_items, hl->items.data(), hl->items.size() * sizeof(WorkItem),
                            hipMemcpyHostToDevice, stream));
-  if (!wl->h_valu_panels.empty())
-    HIP_TRY(hipMemcpyAsync(wl->d_valu_panels, wl->h_valu_panels.data(),
-                           wl->h_valu_panels.size() * sizeof(uint32_t), hipMemcpyHostToDevice,
+  if (!hl->valu_panels.empty())
+    HIP_TRY(hipMemcpyAsync(wl->d_valu_panels, hl->valu_panels.data(),
+                           hl->valu_panels.size() * sizeof(uint32_t), hipMemcpyHostToDevice,
                            stream));
-  if (!merges.empty())
-    HIP_TRY(hipMemcpyAsync(wl->d_merge, merges.data(), merges.size() * sizeof(MergeItem),
+  if (!hl->merges.empty())
+    HIP_TRY(hipMemcpyAsync(wl->d_merge, hl->merges.data(), hl->merges.size() * sizeof(MergeItem),
                            hipMemcpyHostToDevice, stream));
-  HIP_TRY(hipStreamSynchronize(stream));  // the host vectors above go out of scope
+  HIP_TRY(hipStreamSynchronize(stream));
+  try {
+    pl->lists[N] = wl;
+  } catch (const std::bad_alloc&) {
+    status = fail(SPMM_ENOMEM, "host allocation failed");
+  }
 done:
   if (status != SPMM_OK) {
     delete wl;
     return status;
   }
-  pl->lists[N] = wl;
   *out = wl;
   return SPMM_OK;
 }
@@ -379,6 +424,10 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   if (h_err & (kErrRowptrEnds | kErrRowptrOrder)) {
     status = fail(SPMM_EFORMAT, "invalid rowptr (%s)",
                   (h_err & kErrRowptrEnds) ? "rowptr[0] != 0 or rowptr[M] != nnz" : "not monotone");
+    goto done;
+  }
+  if (h_err & (kErrColRange | kErrColOrder)) {   // a panel whose column span is inverted
+    status = fail(SPMM_EFORMAT, "invalid colind (columns of a row not strictly ascending)");
     goto done;
   }
   words_cap = panel_bitmap_words(h_small[1]);
@@ -542,24 +591,42 @@ done:
   return status;
 }
 
-int spmm_exec(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream_) {
+namespace {
+
+int check_exec_args(const spmm_plan_t* pl, const float* B, int64_t N, const float* C) {
   if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
   if (N < 0) return fail(SPMM_EINVAL, "N is negative");
-  if (N == 0 || pl->M == 0) return SPMM_OK;
+  if (N == 0 || pl->M == 0) return 1;   // nothing to do
   if (!C) return fail(SPMM_EINVAL, "C is NULL");
   if (!B && pl->K > 0) return fail(SPMM_EINVAL, "B is NULL");
-  hipStream_t s = (hipStream_t)stream_;
-  WorkList* wl = nullptr;
-  int status = build_worklist(pl, N, s, &wl);
-  if (status != SPMM_OK) return status;
+  return SPMM_OK;
+}
+
+// the three launches of one product; every pointer is a device pointer
+int launch_product(const spmm_plan_t* pl, const HostList* hl, const WorkItem* d_items,
+                   const uint32_t* d_valu_panels, const MergeItem* d_merge, float* d_partial,
+                   const float* B, int64_t N, float* C, hipStream_t s) {
+  int status = SPMM_OK;
   const BrickFormat f{pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals};
-  HIP_TRY(launch_spmm_mfma(f, wl->d_items, wl->info.n_mfma_items, B, C, wl->d_partial, pl->M, N,
-                           pl->K, s));
-  HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, wl->d_valu_panels,
-                           wl->info.n_valu_panels, B, C, pl->M, N, s));
-  HIP_TRY(launch_merge(wl->d_merge, wl->n_merge, wl->d_partial, C, pl->M, N, s));
+  HIP_TRY(launch_spmm_mfma(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K, s));
+  HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, d_valu_panels,
+                           hl->info.n_valu_panels, B, C, pl->M, N, s));
+  HIP_TRY(launch_merge(d_merge, (int64_t)hl->merges.size(), d_partial, C, pl->M, N, s));
 done:
   return status;
+}
+
+}  // namespace
+
+int spmm_exec(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream_) {
+  int status = check_exec_args(pl, B, N, C);
+  if (status != SPMM_OK) return status > 0 ? SPMM_OK : status;
+  hipStream_t s = (hipStream_t)stream_;
+  WorkList* wl = nullptr;
+  status = build_worklist(pl, N, s, &wl);
+  if (status != SPMM_OK) return status;
+  return launch_product(pl, wl->host, wl->d_items, wl->d_valu_panels, wl->d_merge, wl->d_partial,
+                        B, N, C, s);
 }
 
 int spmm_synergy(const spmm_plan_t* pl, int64_t N, spmm_synergy_t* o) {
@@ -632,7 +699,7 @@ int spmm_plan_set_route(spmm_plan_t* pl, int route) {
 
 int spmm_plan_set_split(spmm_plan_t* pl, int parts) {
   if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
-  if (parts < 0) return fail(SPMM_EINVAL, "parts is negative");
+  if (parts < SPMM_SPLIT_EQ7_NEAREST) return fail(SPMM_EINVAL, "unknown split policy");
   if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
   pl->split = parts;
   pl->drop_lists();
@@ -650,13 +717,14 @@ int spmm_plan_set_order(spmm_plan_t* pl, int order) {
 }
 
 int spmm_partition_counts(int64_t n_panels, const uint32_t* nbricks, int64_t work_items,
-                          int32_t num_cus, int32_t resident_per_cu, uint32_t* parts_out,
-                          int64_t* waves_out) {
-  if (n_panels < 0 || work_items < 0 || num_cus < 1 || resident_per_cu < 1)
+                          int32_t num_cus, int32_t resident_per_cu, int32_t policy,
+                          uint32_t* parts_out, int64_t* waves_out) {
+  if (n_panels < 0 || work_items < 0 || num_cus < 1 || resident_per_cu < 1 ||
+      (policy != SPMM_SPLIT_EQ7_FROM2 && policy != SPMM_SPLIT_EQ7_NEAREST))
     return fail(SPMM_EINVAL, "bad argument");
   if (n_panels > 0 && (!nbricks || !parts_out)) return fail(SPMM_EINVAL, "NULL argument");
-  partition_counts(n_panels, nbricks, work_items, (int64_t)num_cus * resident_per_cu, parts_out,
-                   waves_out);
+  partition_counts(n_panels, nbricks, work_items, (int64_t)num_cus * resident_per_cu, policy,
+                   parts_out, waves_out);
   return SPMM_OK;
 }
 
@@ -664,14 +732,14 @@ int spmm_plan_worklist(spmm_plan_t* pl, int64_t N, spmm_worklist_info_t* info,
                        spmm_work_item_t* items, uint32_t* valu_panels) {
   if (!pl || !info) return fail(SPMM_EINVAL, "NULL argument");
   if (N < 1) return fail(SPMM_EINVAL, "N must be positive");
-  WorkList* wl = nullptr;
-  const int status = build_worklist(pl, N, nullptr, &wl);
+  const HostList* hl = nullptr;
+  const int status = build_host_list(pl, N, &hl);
   if (status != SPMM_OK) return status;
-  *info = wl->info;
-  if (items && !wl->h_items.empty())
-    memcpy(items, wl->h_items.data(), wl->h_items.size() * sizeof(spmm_work_item_t));
-  if (valu_panels && !wl->h_valu_panels.empty())
-    memcpy(valu_panels, wl->h_valu_panels.data(), wl->h_valu_panels.size() * sizeof(uint32_t));
+  *info = hl->info;
+  if (items && !hl->h_items.empty())
+    memcpy(items, hl->h_items.data(), hl->h_items.size() * sizeof(spmm_work_item_t));
+  if (valu_panels && !hl->valu_panels.empty())
+    memcpy(valu_panels, hl->valu_panels.data(), hl->valu_panels.size() * sizeof(uint32_t));
   return SPMM_OK;
 }
 

@@ -423,10 +423,10 @@ __device__ inline int row_in_panel(const int32_t* rp, int64_t e) {
 // a valid rowptr.  out[0] = span, out[1] = entries.
 __global__ void k_panel_span(const int32_t* __restrict__ rowptr,
                              const int32_t* __restrict__ colind, int64_t M, int64_t P,
-                             const uint32_t* __restrict__ err, uint32_t* out) {
-  __shared__ uint32_t s_span, s_nnz;
+                             uint32_t* err, uint32_t* out) {
+  __shared__ uint32_t s_span, s_nnz, s_bad;
   if (*err & (kErrRowptrEnds | kErrRowptrOrder)) return;
-  if (threadIdx.x == 0) { s_span = 0; s_nnz = 0; }
+  if (threadIdx.x == 0) { s_span = 0; s_nnz = 0; s_bad = 0; }
   __syncthreads();
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (p < P) {
@@ -437,12 +437,15 @@ __global__ void k_panel_span(const int32_t* __restrict__ rowptr,
       if (s < t) { lo = min(lo, colind[s]); hi = max(hi, colind[t - 1]); }
     }
     if (hi >= lo) atomicMax(&s_span, (uint32_t)((int64_t)hi - lo + 1));
+    else if (rowptr[r1] > rowptr[r0]) atomicOr(&s_bad, 1u);   // entries, but an inverted span
     atomicMax(&s_nnz, (uint32_t)(rowptr[r1] - rowptr[r0]));
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     if (s_span) atomicMax(&out[0], s_span);
     if (s_nnz) atomicMax(&out[1], s_nnz);
+    // a panel whose rows end below where they start is not sorted (or has a negative column)
+    if (s_bad) atomicOr(err, (uint32_t)kErrColOrder);
   }
 }
 
@@ -486,7 +489,14 @@ __global__ __launch_bounds__(kPanelThreads) void k_panel_census(
     if (p == P - 1) panel_nnzptr[P] = (uint32_t)x.e1;
   }
   if (x.e0 >= x.e1 || x.cmax < x.cmin) {
-    if (threadIdx.x == 0) { nbricks_p[p] = 0; ncols_p[p] = 0; }
+    // Entries but an inverted span (the last column of every row lies below the first column
+    // of some row): a row is stored in descending order, or a column is negative.  No bitmap
+    // can hold that, so the per-entry checks below would never see it.
+    if (threadIdx.x == 0) {
+      if (x.e0 < x.e1) atomicOr(err, (uint32_t)kErrColOrder);
+      nbricks_p[p] = 0;
+      ncols_p[p] = 0;
+    }
     return;
   }
   const uint32_t words = (uint32_t)(x.cmax - x.cmin) / 32u + 1u;
@@ -960,7 +970,7 @@ hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long lon
 
 // ---- per-panel path
 hipError_t launch_panel_span(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t P,
-                             const uint32_t* err, uint32_t* span_and_nnz, hipStream_t s) {
+                             uint32_t* err, uint32_t* span_and_nnz, hipStream_t s) {
   if (P == 0) return hipSuccess;
   hipLaunchKernelGGL(k_panel_span, dim3(grid_for(P)), dim3(kThreads), 0, s, rowptr, colind, M, P,
                      err, span_and_nnz);

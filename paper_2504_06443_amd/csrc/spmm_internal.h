@@ -81,8 +81,9 @@ hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long lon
 
 // per-panel path (LDS bitmap over the panel's column span)
 // out[0] = widest column span of a panel, out[1] = most entries of a panel
+// (also flags a panel whose column span is inverted: unsorted rows or negative columns)
 hipError_t launch_panel_span(const int32_t* rowptr, const int32_t* colind, int64_t M, int64_t P,
-                             const uint32_t* err, uint32_t* span_and_nnz, hipStream_t s);
+                             uint32_t* err, uint32_t* span_and_nnz, hipStream_t s);
 // per-panel path by sorting (any column span, panels of limited size)
 uint32_t panel_sort_keys(uint32_t max_nnz);   // 0: a panel has too many entries
 bool panel_sort_build_fits(uint32_t n_cap, uint32_t nb_cap);

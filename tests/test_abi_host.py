@@ -37,7 +37,7 @@ def test_struct_layout_matches_header(binding):
     # 8 + 3*3 + 65 int64, 2 int32, 10 doubles
     assert ctypes.sizeof(binding._Synergy) == 8 * (8 + 9 + 65) + 8 + 8 * 10
     assert ctypes.sizeof(binding._WorkItem) == 20
-    assert ctypes.sizeof(binding._WorklistInfo) == 40
+    assert ctypes.sizeof(binding._WorklistInfo) == 48
 
 
 def test_partition_paper_example(binding, golden_dir):
@@ -52,6 +52,22 @@ def test_partition_paper_example(binding, golden_dir):
     assert parts[0] == g["parts_heavy"] and set(parts[1:].tolist()) == {g["parts_other"]}
 
 
+def test_partition_rounding_examples(binding, golden_dir):
+    """The hand-worked rounding examples of Eq. 7 through the C ABI, both policies."""
+    n = 0
+    for ln in open(os.path.join(golden_dir, "load_balance_rounding.txt")):
+        if not ln.strip() or ln.startswith("#"):
+            continue
+        name, blocks, _, nearest, from2, others = ln.split()
+        bricks = [4 * int(b) for b in blocks.split(",")]
+        for policy, want in ((binding.SPLIT_EQ7_NEAREST, int(nearest)), (binding.SPLIT_EQ7_FROM2, int(from2))):
+            parts, waves = binding.spmm_partition_counts(bricks, len(bricks), 1000, 1, policy)
+            assert waves == 1 and parts[0] == want, (name, policy)
+            assert set(parts[1:].tolist()) == {int(others)}, (name, policy)
+        n += 1
+    assert n >= 8
+
+
 @pytest.mark.parametrize("seed", range(5))
 def test_partition_matches_oracle(binding, seed):
     rng = np.random.default_rng(seed)
@@ -59,9 +75,10 @@ def test_partition_matches_oracle(binding, seed):
     bricks = rng.zipf(1.6, size=P).clip(max=5000).astype(np.uint32)
     bricks[rng.random(P) < 0.1] = 0
     for items, cus, res in ((P, 256, 8), (P, 4, 1), (3 * P, 16, 2)):
-        parts, waves = binding.spmm_partition_counts(bricks, items, cus, res)
-        eparts, ewaves = oracle.partition_counts(bricks.tolist(), items, cus, res)
-        assert waves == ewaves and parts.tolist() == eparts
+        for policy, name in ((binding.SPLIT_EQ7_FROM2, "from2"), (binding.SPLIT_EQ7_NEAREST, "nearest")):
+            parts, waves = binding.spmm_partition_counts(bricks, items, cus, res, policy)
+            eparts, ewaves = oracle.partition_counts(bricks.tolist(), items, cus, res, policy=name)
+            assert waves == ewaves and parts.tolist() == eparts
 
 
 def test_partition_rejects_bad_arguments(binding):
@@ -69,6 +86,8 @@ def test_partition_rejects_bad_arguments(binding):
         binding.spmm_partition_counts([1, 2], 2, 0, 1)
     assert e.value.code == binding.SPMM_EINVAL
     assert "bad argument" in binding.spmm_last_error()
+    with pytest.raises(binding.SpmmError):
+        binding.spmm_partition_counts([1, 2], 2, 1, 1, policy=5)
 
 
 def test_null_plan_is_an_error_not_a_crash(binding):
