@@ -164,18 +164,32 @@ def test_split_panels_merge(gpu, split, N):
     assert np.array_equal(C1, C2)
 
 
-def test_auto_split_matches_oracle_partition(gpu):
-    """The library's Eq. 6-7 split equals the oracle's for the wave count it reports."""
-    A = W.power_law(M=4000, target_nnz=None, cap=2000, alpha=1.6, seed=41)
+@pytest.mark.parametrize("policy", ["from2", "nearest"])
+@pytest.mark.parametrize("M,N", [(4000, 128), (120000, 32), (120000, 512)])
+def test_auto_split_matches_oracle_partition(gpu, policy, M, N):
+    """The library's Eq. 6-7 split equals the oracle's, under both rounding policies, with
+    num_waves = ceil(panels x column tiles / (CUs x resident wavefronts per CU)) formed here
+    from the device's CU count as PyTorch reports it and the kernel occupancy the library
+    states (one, two and several waves of work)."""
+    import torch
+    A = W.power_law(M=M, target_nnz=None, cap=2000, alpha=1.6, seed=41)
     plan = make_plan(gpu, A)
     gpu.spmm_plan_set_route(plan, gpu.ROUTE_MFMA)
-    wl = gpu.spmm_plan_worklist(plan, 128)
+    gpu.spmm_plan_set_split(plan, gpu.SPLIT_EQ7_FROM2 if policy == "from2" else gpu.SPLIT_EQ7_NEAREST)
+    wl = gpu.spmm_plan_worklist(plan, N)
     fmt = gpu.spmm_plan_export(plan)
     nb_p = np.diff(fmt["panel_ptr"].astype(np.int64))
     panels = list(range(len(nb_p)))   # this route sends every panel, empty ones too, to the brick kernel
-    # capacity 1 x 1 and `num_waves` work items reproduce the library's wave count
-    parts, waves = oracle.partition_counts([int(nb_p[p]) for p in panels], wl["num_waves"], 1, 1)
-    assert waves == wl["num_waves"]
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert wl["num_cus"] == cus
+    # 4 SIMDs per CU with at most 8 resident wavefronts each; the kernels run 4-wave workgroups
+    assert wl["resident_waves_per_cu"] in range(4, 33, 4)
+    items = len(panels) * -(-N // wl["n_tile"])
+    want_waves = max(1, -(-items // (cus * wl["resident_waves_per_cu"])))
+    assert wl["num_waves"] == want_waves
+    parts, waves = oracle.partition_counts([int(nb_p[p]) for p in panels], items, cus,
+                                           wl["resident_waves_per_cu"], policy=policy)
+    assert waves == want_waves
     got = {}
     for panel, b0, b1, part, nparts in wl["items"]:
         got.setdefault(panel, []).append((int(b0), int(b1)))
@@ -183,6 +197,11 @@ def test_auto_split_matches_oracle_partition(gpu):
         base = int(fmt["panel_ptr"][p])
         expect = [(base + lo, base + hi) for lo, hi in oracle.partition_ranges(int(nb_p[p]), want)]
         assert sorted(got[p]) == expect, p
+    if M == 4000:
+        assert wl["n_split_panels"] > 0
+        B = W.dense_b(A.K, N, 42)
+        Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+        check_c(run_product(gpu, plan, A, B), Cref, S)
 
 
 def test_invalid_csr_is_rejected(gpu):
@@ -213,6 +232,62 @@ def test_invalid_csr_is_rejected(gpu):
     # and a valid plan still works afterwards
     plan = make_plan(gpu, good)
     assert gpu.spmm_plan_sizes(plan)["nnz"] == good.nnz
+
+
+def test_invalid_rows_on_the_bitmap_path_are_rejected(gpu):
+    """Band-like matrices take the plan's per-panel bitmap path.  A panel whose only row is
+    stored in descending order, or holds a column beyond K before a small one, has an inverted
+    column span (last column of every row below the first column of some row): no bitmap is
+    built for it, and it must still be rejected, not silently dropped."""
+    import torch
+    base = W.tiny_banded(M=640, seed=3)           # bitmap path: narrow spans, many entries
+
+    def with_panel_replaced(panel, cols):
+        keep = (np.repeat(np.arange(base.M), np.diff(base.rowptr)) // 16) != panel
+        rows = np.repeat(np.arange(base.M), np.diff(base.rowptr))[keep]
+        rp = np.zeros(base.M + 1, np.int64)
+        np.add.at(rp, rows + 1, 1)
+        rp[16 * panel + 1] += len(cols)
+        rp = np.cumsum(rp).astype(np.int32)
+        ci = np.concatenate([base.colind[keep][:rp[16 * panel]], np.asarray(cols, np.int32),
+                             base.colind[keep][rp[16 * panel]:]]).astype(np.int32)
+        return rp, ci, np.ones(len(ci), np.float32)
+
+    cases = {
+        "single_descending_row": with_panel_replaced(5, [7, 3]),
+        "single_row_out_of_range_then_small": with_panel_replaced(9, [base.K + 5, 2]),
+        "negative_then_valid": with_panel_replaced(0, [4, -1]),
+        "last_panel_descending": with_panel_replaced(39, [600, 599, 598]),
+    }
+    # all 16 rows of a panel descending
+    rp, ci, v = with_panel_replaced(7, [])
+    rows16 = []
+    for r in range(16):
+        rows16.append([200 + r + 2, 200 + r])
+    rp2 = rp.astype(np.int64).copy()
+    add = np.zeros(base.M + 1, np.int64)
+    for r in range(16):
+        add[16 * 7 + r + 1:] += 2
+    at = int(rp[16 * 7])
+    cases["sixteen_descending_rows"] = ((rp2 + add).astype(np.int32),
+                                        np.concatenate([ci[:at], np.asarray(rows16, np.int32).ravel(),
+                                                        ci[at:]]).astype(np.int32),
+                                        np.ones(len(ci) + 32, np.float32))
+    for name, (rp_, ci_, v_) in cases.items():
+        print("invalid bitmap-path case", name, flush=True)
+        assert rp_[-1] == len(ci_) == len(v_)
+        with pytest.raises(gpu.SpmmError) as e:
+            gpu.spmm_plan(base.M, base.K, torch.from_numpy(rp_).cuda(), torch.from_numpy(ci_).cuda(),
+                          torch.from_numpy(v_).cuda())
+        assert e.value.code == gpu.SPMM_EFORMAT, name
+    with pytest.raises(ValueError):     # the binding checks the array lengths before the call
+        gpu.spmm_plan(base.M, base.K, torch.from_numpy(base.rowptr[:-1].copy()).cuda(),
+                      torch.from_numpy(base.colind).cuda(), torch.from_numpy(base.vals).cuda())
+    with pytest.raises(ValueError):
+        gpu.spmm_plan(base.M, base.K, torch.from_numpy(base.rowptr).cuda(),
+                      torch.from_numpy(base.colind).cuda(), torch.from_numpy(base.vals[:-1].copy()).cuda())
+    plan = make_plan(gpu, base)          # the untouched matrix still plans
+    assert gpu.spmm_plan_sizes(plan)["nnz"] == base.nnz
 
 
 def test_degenerate_sizes(gpu):
@@ -312,6 +387,8 @@ def test_error_paths_on_device(gpu):
     assert "NULL" in gpu.spmm_last_error()
     assert lib.spmm_plan_set_route(plan._h, 7) == gpu.SPMM_EINVAL
     assert lib.spmm_plan_set_split(plan._h, -2) == gpu.SPMM_EINVAL
+    assert lib.spmm_plan_set_split(plan._h, gpu.SPLIT_EQ7_NEAREST) == gpu.SPMM_OK
+    assert lib.spmm_plan_set_split(plan._h, gpu.SPLIT_EQ7_FROM2) == gpu.SPMM_OK
     with pytest.raises(ValueError):
         gpu.spmm_exec(plan, torch.zeros((31, 8), device="cuda"))
     # nnz that disagrees with rowptr[M]
