@@ -110,6 +110,29 @@ int spmm_plan_update_values(spmm_plan_t *plan, const float *vals, void *stream);
 int spmm_exec(spmm_plan_t *plan, const float *B, int64_t N, float *C, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * spmm_exec_noalloc -- the same product for callers that cannot allocate device
+ * memory: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Arguments, result and kernels are those of spmm_exec (bit-identical C),
+ * but the call makes no hipMalloc / hipFree, not even on its first use for a new N:
+ * the work list of the MFMA kernel and the partial tiles of split panels live in one
+ * static device array of 32 MiB per GPU (held until the process ends) instead of
+ * plan-owned allocations.
+ *
+ *   - Work list plus partial tiles (16 x N floats per part of a split panel) must fit
+ *     the 32 MiB; otherwise SPMM_ELIMIT with the sizes in spmm_last_error(), and
+ *     nothing is enqueued.
+ *   - The array keeps the work list of the last (plan, N) that used it on this GPU;
+ *     a call with another plan or N first copies its list in with hipMemcpyAsync on
+ *     `stream` (from host memory the plan owns), a repeat call copies nothing and
+ *     only enqueues kernels.  Partial tiles are fully overwritten before they are
+ *     read, so nothing needs clearing.
+ *   - All calls on one GPU share the array: two calls that overlap in time on one
+ *     GPU (different streams, different plans) race.  Order them.
+ *   - Uses the current device; the array's address is looked up once per device.
+ */
+int spmm_exec_noalloc(spmm_plan_t *plan, const float *B, int64_t N, float *C, void *stream);
+
+/* ---------------------------------------------------------------------------
  * spmm_synergy -- brick density, modeled operational intensity and synergy class
  * (Section 4, Eq. 4; Section 6.4, Table 1), plus an HBM / MFMA roofline model
  * for MI355X.  Pure host arithmetic on counts gathered at plan time.

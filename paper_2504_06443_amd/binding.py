@@ -31,7 +31,7 @@ SPLIT_EQ7_NEAREST, SPLIT_EQ7_FROM2, SPLIT_NEVER = -1, 0, 1
 CLASS_NAMES = ("Low", "Medium", "High")
 
 EXPORTED = (
-    "spmm_plan", "spmm_plan_update_values", "spmm_exec", "spmm_synergy",
+    "spmm_plan", "spmm_plan_update_values", "spmm_exec", "spmm_exec_noalloc", "spmm_synergy",
     "spmm_plan_sizes",
     "spmm_plan_export",
     "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_partition_counts",
@@ -82,6 +82,7 @@ _lib.spmm_last_error.restype = C.c_char_p
 _lib.spmm_plan.argtypes = [C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, C.POINTER(_vp)]
 _lib.spmm_plan_update_values.argtypes = [_vp, _vp, _vp]
 _lib.spmm_exec.argtypes = [_vp, _vp, C.c_int64, _vp, _vp]
+_lib.spmm_exec_noalloc.argtypes = [_vp, _vp, C.c_int64, _vp, _vp]
 _lib.spmm_synergy.argtypes = [_vp, C.c_int64, C.POINTER(_Synergy)]
 _lib.spmm_plan_sizes.argtypes = [_vp, C.POINTER(_Sizes)]
 _lib.spmm_plan_export.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
@@ -167,6 +168,12 @@ def spmm_exec(plan: Plan, B, C_out=None, stream=None, _entry=None):
     _check(entry(plan._h, _dev(B, torch.float32) if B.numel() else None, N,
                  _dev(C_out, torch.float32) if C_out.numel() else None, _stream_ptr(stream)))
     return C_out
+
+
+def spmm_exec_noalloc(plan: Plan, B, C_out, stream=None):
+    """Same product through the entry point that allocates no device memory; the caller
+    provides C (allocating it here would defeat the purpose)."""
+    return spmm_exec(plan, B, C_out, stream, _entry=_lib.spmm_exec_noalloc)
 
 
 def spmm_synergy(plan: Plan, N: int) -> dict:

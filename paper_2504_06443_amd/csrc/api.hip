@@ -11,6 +11,7 @@
 #include <cstring>
 #include <atomic>
 #include <map>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -321,6 +322,42 @@ done:
   return SPMM_OK;
 }
 
+// ---- static scratch of spmm_exec_noalloc ------------------------------------------------
+// One array per GPU, held until the process ends.  It carries what spmm_exec keeps in
+// plan-owned allocations: the work list of the last (plan, N) that used it and the partial
+// tiles of split panels.  In host code `scratch` is only a handle for hipGetSymbolAddress;
+// the device address is looked up once per device and used everywhere else.
+constexpr size_t kScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+struct ScratchState {
+  unsigned char* ptr = nullptr;   // device address of this GPU's copy of `scratch`
+  uint64_t list_id = 0;           // HostList whose items the array currently holds (0: none)
+};
+ScratchState g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+size_t pad256(size_t b) { return (b + 255) & ~size_t(255); }
+
+// Device address of the current device's copy of `scratch`, looked up on first use per device
+// (the runtime materialises the array then; spmm_plan does this so that spmm_exec_noalloc
+// itself never changes the amount of free device memory).  Caller holds g_scratch_mutex.
+int scratch_state(ScratchState** out) {
+  int status = SPMM_OK;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SPMM_ELIMIT, "device index %d not supported", dev);
+  if (!g_scratch[dev].ptr) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch[dev].ptr = static_cast<unsigned char*>(p);
+  }
+  *out = &g_scratch[dev];
+done:
+  return status;
+}
+
 }  // namespace
 
 extern "C" {
@@ -386,6 +423,12 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   };
 
   HIP_TRY(hipGetDevice(&pl->device));
+  {   // set-up of the allocation-free entry point: resolve this device's static scratch once
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ScratchState* st = nullptr;
+    status = scratch_state(&st);
+    if (status != SPMM_OK) goto done;
+  }
   HIP_TRY(hipDeviceGetAttribute(&pl->num_cus, hipDeviceAttributeMultiprocessorCount, pl->device));
   pl->num_cus = std::max(1, pl->num_cus);
 
@@ -627,6 +670,60 @@ int spmm_exec(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream
   if (status != SPMM_OK) return status;
   return launch_product(pl, wl->host, wl->d_items, wl->d_valu_panels, wl->d_merge, wl->d_partial,
                         B, N, C, s);
+}
+
+int spmm_exec_noalloc(spmm_plan_t* pl, const float* B, int64_t N, float* C, void* stream_) {
+  int status = check_exec_args(pl, B, N, C);
+  if (status != SPMM_OK) return status > 0 ? SPMM_OK : status;
+  hipStream_t s = (hipStream_t)stream_;
+  const HostList* hl = nullptr;
+  status = build_host_list(pl, N, &hl);   // host arithmetic only; cached per N
+  if (status != SPMM_OK) return status;
+
+  const size_t items_b = pad256(hl->items.size() * sizeof(WorkItem));
+  const size_t valu_b = pad256(hl->valu_panels.size() * sizeof(uint32_t));
+  const size_t merge_b = pad256(hl->merges.size() * sizeof(MergeItem));
+  const size_t partial_b = (size_t)hl->n_slots * kPanel * (size_t)N * sizeof(float);
+  if (items_b + valu_b + merge_b + partial_b > kScratchBytes)
+    return fail(SPMM_ELIMIT,
+                "spmm_exec_noalloc: work list (%zu B) and partial tiles of split panels (%zu B) "
+                "exceed the static scratch of %zu B; use spmm_exec",
+                items_b + valu_b + merge_b, partial_b, kScratchBytes);
+
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ScratchState* stp = nullptr;
+    status = scratch_state(&stp);
+    if (status != SPMM_OK) return status;
+    ScratchState& st = *stp;
+    unsigned char* base = st.ptr;
+    WorkItem* d_items = reinterpret_cast<WorkItem*>(base);
+    uint32_t* d_valu = reinterpret_cast<uint32_t*>(base + items_b);
+    MergeItem* d_merge = reinterpret_cast<MergeItem*>(base + items_b + valu_b);
+    float* d_partial = reinterpret_cast<float*>(base + items_b + valu_b + merge_b);
+    if (st.list_id != hl->id) {
+      // the array holds another list: bring this one in (copies from plan-owned host memory
+      // that lives as long as the list; ordered on `s` before the kernels below)
+      st.list_id = 0;
+      if (!hl->items.empty())
+        HIP_TRY(hipMemcpyAsync(d_items, hl->items.data(), hl->items.size() * sizeof(WorkItem),
+                               hipMemcpyHostToDevice, s));
+      if (!hl->valu_panels.empty())
+        HIP_TRY(hipMemcpyAsync(d_valu, hl->valu_panels.data(),
+                               hl->valu_panels.size() * sizeof(uint32_t), hipMemcpyHostToDevice, s));
+      if (!hl->merges.empty())
+        HIP_TRY(hipMemcpyAsync(d_merge, hl->merges.data(), hl->merges.size() * sizeof(MergeItem),
+                               hipMemcpyHostToDevice, s));
+      st.list_id = hl->id;
+    }
+    // Partial tiles need no clearing: every part of a split panel overwrites its whole tile
+    // before the merge kernel reads it.
+    status = launch_product(pl, hl, d_items, d_valu, d_merge, hl->n_slots ? d_partial : nullptr,
+                            B, N, C, s);
+    if (status != SPMM_OK) st.list_id = 0;
+  }
+done:
+  return status;
 }
 
 int spmm_synergy(const spmm_plan_t* pl, int64_t N, spmm_synergy_t* o) {

@@ -93,6 +93,7 @@ def test_partition_rejects_bad_arguments(binding):
 def test_null_plan_is_an_error_not_a_crash(binding):
     import ctypes
     assert binding._lib.spmm_exec(None, None, 4, None, None) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_exec_noalloc(None, None, 4, None, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_synergy(None, 4, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_plan_sizes(None, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_plan_update_values(None, None, None) == binding.SPMM_EINVAL
