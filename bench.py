@@ -141,6 +141,8 @@ def measure(spmm, name, N, steps, warmup, route="auto", split=0, order="panel", 
     spmm.spmm_plan_set_route(plan, ROUTES[route])
     spmm.spmm_plan_set_split(plan, split)
     spmm.spmm_plan_set_order(plan, 1 if order == "heavy" else 0)
+    if mode != "fp32":
+        spmm.spmm_plan_set_precision(plan, spmm.PRECISIONS[mode])
     syn = spmm.spmm_synergy(plan, N)
     wl = spmm.spmm_plan_worklist(plan, N)
 
@@ -248,8 +250,9 @@ def main():
                     help="0: Eq. 6-7, split from ratio 2; -1: Eq. 6-7, nearest; 1: never; k: force k")
     ap.add_argument("--order", default="panel", choices=["panel", "heavy"],
                     help="work-item order: panel order, or heaviest first (the schedule the paper rejects)")
-    ap.add_argument("--mode", default="fp32", choices=["fp32"],
-                    help="arithmetic of the brick kernel")
+    ap.add_argument("--mode", default="fp32", choices=["fp32", "bf16x3", "bf16x6"],
+                    help="arithmetic of the brick kernel: fp32 (default), or the opt-in split-bf16 "
+                         "modes (three / six bf16 products per FP32 product)")
     ap.add_argument("--cold", action="store_true",
                     help="rotate over several B/C pairs so that no step finds its operands in cache")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")

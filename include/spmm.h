@@ -210,6 +210,29 @@ int spmm_plan_set_split(spmm_plan_t *plan, int parts);
 enum spmm_order { SPMM_ORDER_PANEL = 0, SPMM_ORDER_HEAVY_FIRST = 1 };
 int spmm_plan_set_order(spmm_plan_t *plan, int order);
 
+/* Arithmetic of the MFMA brick kernel.  The paper rounds its FP32 inputs to TF32 (10-bit
+ * mantissa) and accumulates in FP32 (Section 2, "Background"); that buys its tensor cores an
+ * eightfold rate over the ordinary ALUs.  gfx950's FP32 MFMA has no such advantage, so
+ * matrices of Medium synergy are bound by zero-filled FP32 MFMA work.  The opt-in modes below
+ * move that work to the bf16 matrix cores while keeping more mantissa than TF32: each FP32
+ * input is split into a sum of bf16 numbers and the leading partial products are accumulated
+ * in FP32.
+ *   SPMM_PRECISION_FP32    v_mfma_f32_16x16x4_f32 on the unrounded inputs (default);
+ *                          |C - C_exact| <= 1e-5 * sum|a.b| for the sizes tested
+ *   SPMM_PRECISION_BF16X3  two bf16 terms per input (8 significant bits each, so what they
+ *                          leave of a number is at most 2^-16 of it), three products
+ *                          (a1 b1 + a1 b2 + a2 b1); the three dropped terms are at most
+ *                          2^-16 |a.b| each: |C - C_exact| <= 5e-5 * sum|a.b|
+ *                          (TF32 rounding of both inputs: about 1e-3)
+ *   SPMM_PRECISION_BF16X6  three bf16 terms per input, six products; dropped terms are at
+ *                          most 2^-24 |a.b| each: the same 1e-5 bound as FP32
+ * The modes apply to the MFMA kernel when N is a multiple of 4 (of N itself below 64:
+ * of the vector width), B and C are 16-byte aligned, B is smaller than 4 GiB and K <= 2^24;
+ * other shapes, and the CSR kernel, compute in FP32.  Inputs must be finite and their
+ * products within FP32 range.  Drops cached work lists. */
+enum spmm_precision { SPMM_PRECISION_FP32 = 0, SPMM_PRECISION_BF16X3 = 1, SPMM_PRECISION_BF16X6 = 2 };
+int spmm_plan_set_precision(spmm_plan_t *plan, int precision);
+
 /* Host-only arithmetic of Eq. 6-7; needs no GPU.
  *   n_panels, nbricks[n_panels]  bricks per panel (a block is 4 bricks)
  *   work_items   thread-block count before splitting ("Total_thread_blocks")

@@ -28,13 +28,16 @@ SPMM_OK, SPMM_EINVAL, SPMM_EFORMAT, SPMM_ENOMEM, SPMM_EHIP, SPMM_ELIMIT = 0, -1,
 ROUTE_AUTO, ROUTE_MFMA, ROUTE_VALU, ROUTE_CLASS = 0, 1, 2, 3
 ORDER_PANEL, ORDER_HEAVY_FIRST = 0, 1
 SPLIT_EQ7_NEAREST, SPLIT_EQ7_FROM2, SPLIT_NEVER = -1, 0, 1
+PRECISION_FP32, PRECISION_BF16X3, PRECISION_BF16X6 = 0, 1, 2
+PRECISIONS = {"fp32": PRECISION_FP32, "bf16x3": PRECISION_BF16X3, "bf16x6": PRECISION_BF16X6}
 CLASS_NAMES = ("Low", "Medium", "High")
 
 EXPORTED = (
     "spmm_plan", "spmm_plan_update_values", "spmm_exec", "spmm_exec_noalloc", "spmm_synergy",
     "spmm_plan_sizes",
     "spmm_plan_export",
-    "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_partition_counts",
+    "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_plan_set_precision",
+    "spmm_partition_counts",
     "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error",
 )
 
@@ -89,6 +92,7 @@ _lib.spmm_plan_export.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.spmm_plan_set_route.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_split.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_order.argtypes = [_vp, C.c_int]
+_lib.spmm_plan_set_precision.argtypes = [_vp, C.c_int]
 _lib.spmm_partition_counts.argtypes = [C.c_int64, _vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                        _vp, C.POINTER(C.c_int64)]
 _lib.spmm_plan_worklist.argtypes = [_vp, C.c_int64, C.POINTER(_WorklistInfo), _vp, _vp]
@@ -221,6 +225,10 @@ def spmm_plan_set_split(plan: Plan, parts: int):
 
 def spmm_plan_set_order(plan: Plan, order: int):
     _check(_lib.spmm_plan_set_order(plan._h, order))
+
+
+def spmm_plan_set_precision(plan: Plan, precision: int):
+    _check(_lib.spmm_plan_set_precision(plan._h, precision))
 
 
 def spmm_partition_counts(nbricks, work_items: int, num_cus: int, resident_per_cu: int,

@@ -97,6 +97,7 @@ struct spmm_plan {
   int route = SPMM_ROUTE_AUTO;
   int split = 0;
   int order = SPMM_ORDER_PANEL;
+  int precision = SPMM_PRECISION_FP32;
   std::map<int64_t, HostList*> host_lists;
   std::map<int64_t, WorkList*> lists;
 
@@ -210,7 +211,12 @@ int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
     const int64_t nm = (int64_t)mfma_panels.size();
     std::vector<uint32_t> parts((size_t)nm, 1u);
     int64_t waves = 1;
-    const int resident = mfma_resident_waves_per_cu(std::max<int64_t>(N, 1), pl->K);
+    const bool bf16 = pl->precision != SPMM_PRECISION_FP32 &&
+                      bf16_path_shape(std::max<int64_t>(N, 1), pl->K);
+    const int resident =
+        bf16 ? bf16_resident_waves_per_cu(std::max<int64_t>(N, 1),
+                                          pl->precision == SPMM_PRECISION_BF16X3 ? 2 : 3)
+             : mfma_resident_waves_per_cu(std::max<int64_t>(N, 1), pl->K);
     hl->info.resident_waves_per_cu = resident;
     if (nm > 0) {
       if (pl->split == SPMM_SPLIT_EQ7_FROM2 || pl->split == SPMM_SPLIT_EQ7_NEAREST) {
@@ -636,6 +642,8 @@ done:
 
 namespace {
 
+bool ptr_is_aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
 int check_exec_args(const spmm_plan_t* pl, const float* B, int64_t N, const float* C) {
   if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
   if (N < 0) return fail(SPMM_EINVAL, "N is negative");
@@ -651,7 +659,18 @@ int launch_product(const spmm_plan_t* pl, const HostList* hl, const WorkItem* d_
                    const float* B, int64_t N, float* C, hipStream_t s) {
   int status = SPMM_OK;
   const BrickFormat f{pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals};
-  HIP_TRY(launch_spmm_mfma(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K, s));
+  {
+    const int tile = mfma_tile_for(N);
+    const int V = tile >= 64 ? 4 : tile / 16;
+    const bool aligned = N % V == 0 && ptr_is_aligned16(B) && ptr_is_aligned16(C) &&
+                         (d_partial == nullptr || ptr_is_aligned16(d_partial));
+    if (pl->precision != SPMM_PRECISION_FP32 && aligned && bf16_path_shape(N, pl->K))
+      HIP_TRY(launch_spmm_bf16(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K,
+                               pl->precision == SPMM_PRECISION_BF16X3 ? 2 : 3, pl->nnz, s));
+    else
+      HIP_TRY(launch_spmm_mfma(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K,
+                               s));
+  }
   HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, d_valu_panels,
                            hl->info.n_valu_panels, B, C, pl->M, N, s));
   HIP_TRY(launch_merge(d_merge, (int64_t)hl->merges.size(), d_partial, C, pl->M, N, s));
@@ -800,6 +819,16 @@ int spmm_plan_set_split(spmm_plan_t* pl, int parts) {
   if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
   pl->split = parts;
   pl->drop_lists();
+  return SPMM_OK;
+}
+
+int spmm_plan_set_precision(spmm_plan_t* pl, int precision) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (precision < SPMM_PRECISION_FP32 || precision > SPMM_PRECISION_BF16X6)
+    return fail(SPMM_EINVAL, "unknown precision");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
+  pl->precision = precision;
+  pl->drop_lists();   // the kernels differ in occupancy, which Eq. 7 uses
   return SPMM_OK;
 }
 

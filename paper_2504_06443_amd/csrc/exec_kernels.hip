@@ -27,7 +27,7 @@
 // row, one coalesced B-row load and one FMA per stored entry.  Used for empty
 // panels (zero fill) and, under the class-based routing, for panels whose brick
 // density is in the Low class of Table 1.
-#include "spmm_internal.h"
+#include "exec_common.h"
 
 namespace spmm {
 
@@ -35,42 +35,9 @@ int mfma_tile_for(int64_t N) { return N <= 16 ? 16 : (N <= 32 ? 32 : (N <= 64 ? 
 
 namespace {
 
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef float float2_t __attribute__((ext_vector_type(2)));
-
-constexpr int kWavesPerBlock = 4;
-constexpr int kXcds = 8;     // accelerator complex dies of an MI355X, each with its own L2
 constexpr int kStages = 4;   // bricks whose loads are in flight per wavefront (MFMA kernel)
 constexpr int kChunk = 16;   // bricks per coalesced metadata fetch
 static_assert(kChunk % kStages == 0 && kChunk == 16, "stage and lane mapping assume this");
-
-template <int V> struct Vec;
-template <> struct Vec<1> { typedef float type; };
-template <> struct Vec<2> { typedef float2_t type; };
-template <> struct Vec<4> { typedef float4_t type; };
-
-template <int V>
-__device__ inline void load_vec(const float* __restrict__ p, float (&out)[V]) {
-  typedef typename Vec<V>::type vt;
-  const vt v = *reinterpret_cast<const vt*>(p);
-  if constexpr (V == 1) out[0] = v;
-  else {
-#pragma unroll
-    for (int w = 0; w < V; ++w) out[w] = v[w];
-  }
-}
-
-template <int V>
-__device__ inline void store_vec(float* __restrict__ p, const float (&in)[V]) {
-  typedef typename Vec<V>::type vt;
-  vt v;
-  if constexpr (V == 1) v = in[0];
-  else {
-#pragma unroll
-    for (int w = 0; w < V; ++w) v[w] = in[w];
-  }
-  *reinterpret_cast<vt*>(p) = v;
-}
 
 // T floats of one B row for this lane: NV vectors of V floats.
 // ALIGNED: N % V == 0 and 16-byte aligned base, so a vector is entirely inside
@@ -105,12 +72,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma(
   constexpr int V = T < 4 ? T : 4;
   constexpr int NV = T / V;
   const int lane = threadIdx.x & 63;
-  // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own
-  // L2.  Give each XCD a contiguous range of work items, so that neighbouring
-  // panels -- which share most of their B rows in banded matrices -- meet in one
-  // L2 instead of every XCD fetching every B row.
-  const uint32_t per_xcd = gridDim.x / kXcds;  // the launcher pads gridDim.x to a multiple
-  const uint32_t vblock = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  const uint32_t vblock = xcd_contiguous_block();   // contiguous range of work items per XCD
   const int64_t item_id = (int64_t)vblock * kWavesPerBlock + (threadIdx.x >> 6);
   if (item_id >= n_items) return;  // whole wavefront leaves together
   const WorkItem it = items[item_id];
@@ -269,9 +231,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
   static_assert(CH % R == 0 && CH * kBrickK <= 64, "stage and lane mapping assume this");
 
   const int lane = threadIdx.x & 63;
-  // contiguous range of work items per XCD (workgroups go to XCDs round-robin)
-  const uint32_t per_xcd = gridDim.x / kXcds;
-  const uint32_t vblock = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  const uint32_t vblock = xcd_contiguous_block();   // contiguous range of work items per XCD
   const int64_t item_id = (int64_t)vblock * kWavesPerBlock + (threadIdx.x >> 6);
   if (item_id >= n_items) return;  // whole wavefront leaves together
   const WorkItem it = items[item_id];
@@ -557,8 +517,6 @@ int occupancy_fast_t() {
     nb = 1;
   return nb * kWavesPerBlock;
 }
-
-bool ptr_aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 // the fast kernel serves N that is a multiple of the vector width with B below 4 GiB
 bool fast_path_shape(int64_t N, int64_t K) {

@@ -136,6 +136,12 @@ int mfma_resident_waves_per_cu(int64_t N, int64_t K);
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
                             int64_t K, hipStream_t s);
+// split-bf16 variant (exec_bf16.hip): planes = 2 or 3 bf16 terms per FP32 input
+bool bf16_path_shape(int64_t N, int64_t K);
+int bf16_resident_waves_per_cu(int64_t N, int planes);
+hipError_t launch_spmm_bf16(const BrickFormat& f, const WorkItem* items, int64_t n_items,
+                            const float* B, float* C, float* partial, int64_t M, int64_t N,
+                            int64_t K, int planes, int64_t nnz, hipStream_t s);
 hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const float* vals,
                             const uint32_t* panels, int64_t n_panels, const float* B, float* C,
                             int64_t M, int64_t N, hipStream_t s);
