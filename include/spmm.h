@@ -34,11 +34,12 @@ enum spmm_status {
 };
 
 enum spmm_route {
-  SPMM_ROUTE_AUTO = 0,  /* the measured policy for MI355X: every panel through the MFMA brick
-                           kernel (it beats the CSR kernel in every synergy class here, because
-                           a panel loads each B row once while CSR loads it once per entry; an
-                           empty panel is a work item without bricks that stores zeros)       */
-  SPMM_ROUTE_MFMA = 1,  /* same routing as AUTO today; stays fixed if AUTO's policy changes   */
+  SPMM_ROUTE_AUTO = 0,  /* the measured policy for MI355X: the MFMA brick kernel for every
+                           panel (it loads each B row of a panel once, CSR loads it once per
+                           entry), except that panels of Low synergy (Table 1) go to the CSR
+                           kernel when N <= 32, where a brick feeds only one or two MFMAs    */
+  SPMM_ROUTE_MFMA = 1,  /* every panel through the MFMA brick kernel (an empty panel is a work
+                           item without bricks that stores zeros)                            */
   SPMM_ROUTE_VALU = 2,  /* every panel through the vector-ALU CSR kernel                      */
   SPMM_ROUTE_CLASS = 3  /* the paper's rule per panel: Low synergy (Table 1) -> CSR kernel,
                            Medium/High -> MFMA brick kernel                                   */

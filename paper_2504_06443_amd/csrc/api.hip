@@ -88,6 +88,8 @@ struct spmm_plan {
   int32_t* colind = nullptr;
   float* csr_vals = nullptr;
   uint32_t* ent_pos = nullptr;    // packed position of each CSR entry (value-only updates)
+  uint32_t* long_rows = nullptr;  // rows with more than long_row_threshold() entries
+  int64_t n_long_rows = 0;
   // host copies used by the work-list builder and the synergy model
   std::vector<uint32_t> h_panel_ptr;
   std::vector<uint32_t> h_panel_nnzptr;   // first CSR entry of each panel
@@ -192,13 +194,19 @@ int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
     for (int64_t p = 0; p < pl->P; ++p) {
       const uint8_t cls = pl->h_panel_class[p];
       bool to_mfma;
+      // AUTO is the measured policy for MI355X: the brick kernel wins wherever a B row is
+      // worth loading once per panel instead of once per entry, which is everywhere except
+      // Low-synergy panels (Table 1) at narrow N, where a brick feeds only one or two MFMAs
+      // and the CSR kernel packs 8 or 16 rows into a wavefront.
+      const bool low_to_csr = N <= 32;
       // an empty panel only needs its rows of C zeroed; either kernel does that, so it goes
-      // where the other panels go and does not cost a second launch
-      if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_AUTO || pl->route == SPMM_ROUTE_MFMA;
+      // where it does not cost a launch of its own
+      if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_MFMA ||
+                                (pl->route == SPMM_ROUTE_AUTO && !low_to_csr);
       else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
       else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
       else if (pl->route == SPMM_ROUTE_CLASS) to_mfma = cls != SPMM_LOW;
-      else to_mfma = true;  // AUTO: the brick kernel is the faster one for every class on MI355X
+      else to_mfma = !(cls == SPMM_LOW && low_to_csr);
       if (to_mfma) {
         mfma_panels.push_back((uint32_t)p);
         nbricks.push_back(pl->h_panel_ptr[p + 1] - pl->h_panel_ptr[p]);
@@ -453,7 +461,8 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   counters = scratch.take<unsigned long long>(kNumCounters);
   d_active = scratch.take<unsigned long long>(1);
 
-  fixed.cap = need(P + 1, 4) + need(M + 1, 4) + 3 * need(nnz, 4);
+  fixed.cap = need(P + 1, 4) + need(M + 1, 4) + 3 * need(nnz, 4) +
+              need(nnz / long_row_threshold() + 1, 4);
   HIP_TRY(hipMalloc((void**)&fixed.base, fixed.cap));
   pl->fixed_arena = fixed.base;
   pl->panel_ptr = fixed.take<uint32_t>(P + 1);
@@ -461,6 +470,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   pl->colind = fixed.take<int32_t>(nnz);
   pl->csr_vals = fixed.take<float>(nnz);
   pl->ent_pos = fixed.take<uint32_t>(nnz);
+  pl->long_rows = fixed.take<uint32_t>(nnz / long_row_threshold() + 1);
 
   // ---- rowptr validation and the widest panel span (device), before anything trusts rowptr
   HIP_TRY(hipMemsetAsync(d_err, 0, 4 * sizeof(uint32_t), s));
@@ -597,6 +607,8 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(launch_panel_classes(pl->panel_ptr, panel_nnzptr, P, panel_class, counters, s));
   HIP_TRY(launch_brick_hist(pl->brick_mask, pl->nb, counters, s));
   HIP_TRY(launch_count_flags(col_seen, K, counters + kCntDistinctCols, s));
+  HIP_TRY(launch_find_long_rows(rowptr, M, long_row_threshold(), pl->long_rows,
+                                counters + kCntLongRows, s));
 
   // ---- host copies for the work-list builder and the model
   try {
@@ -617,6 +629,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(hipMemcpyAsync(pl->h_counters, counters, kNumCounters * sizeof(unsigned long long),
                          hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  pl->n_long_rows = (int64_t)pl->h_counters[kCntLongRows];
 
 done:
   if (status != SPMM_OK) (void)hipStreamSynchronize(s);
@@ -672,7 +685,8 @@ int launch_product(const spmm_plan_t* pl, const HostList* hl, const WorkItem* d_
                                s));
   }
   HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, d_valu_panels,
-                           hl->info.n_valu_panels, B, C, pl->M, N, s));
+                           hl->info.n_valu_panels, pl->long_rows, pl->n_long_rows, B, C, pl->M, N,
+                           s));
   HIP_TRY(launch_merge(d_merge, (int64_t)hl->merges.size(), d_partial, C, pl->M, N, s));
 done:
   return status;

@@ -23,13 +23,16 @@
 // in flight; brick metadata is fetched 16 bricks at a time with coalesced loads
 // and distributed by cross-lane reads.
 //
-// Vector-ALU CSR kernel (the paper's "scalar core" path): one wavefront per
-// row, one coalesced B-row load and one FMA per stored entry.  Used for empty
-// panels (zero fill) and, under the class-based routing, for panels whose brick
-// density is in the Low class of Table 1.
+// Vector-ALU CSR kernels (the paper's "scalar core" path): one B-row load and one FMA per
+// stored entry, no zero filling and no reuse of B rows inside a panel.  Rows are processed
+// side by side in a wavefront (k_spmm_valu_rows), very long rows by a workgroup each
+// (k_spmm_valu_long); k_spmm_valu (one wavefront per row) serves widths that are not a
+// multiple of four.  Used for the panels that the routing sends to the CSR path.
 #include "exec_common.h"
 
 namespace spmm {
+
+int long_row_threshold() { return 256; }
 
 int mfma_tile_for(int64_t N) { return N <= 16 ? 16 : (N <= 32 ? 32 : (N <= 64 ? 64 : 128)); }
 
@@ -462,6 +465,127 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu(
   }
 }
 
+// ------------------------------------------------------------------ VALU CSR, rows side by side
+// Several rows per wavefront: a group of LPR lanes owns one row and covers 4*LPR columns of C
+// (one dwordx4 per lane and stored entry), so a wavefront works on 64/LPR rows at once: two rows
+// at N = 128, eight at N = 32, a whole panel at N = 16.  Column index and value of an entry are
+// fetched LPR at a time with coalesced loads and handed out across the group's lanes.
+// Four entries are in flight per group and iteration; past the end of a row the last entry is
+// re-read with a zero multiplier.  Rows longer than kLongRow entries are left to
+// k_spmm_valu_long, which spreads one row over a whole workgroup.
+constexpr int kLongRow = 256;   // == long_row_threshold()
+
+template <int LPR>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu_rows(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
+    const float* __restrict__ vals, const uint32_t* __restrict__ panels, int64_t n_panels,
+    const float* __restrict__ B, float* __restrict__ C, int64_t M, int64_t N) {
+  constexpr int R = 64 / LPR;              // rows per wavefront
+  constexpr int WPP = kPanel / R;          // wavefronts per panel (R <= 16)
+  const int lane = threadIdx.x & 63;
+  const int64_t wid = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int64_t pslot = wid / WPP;
+  if (pslot >= n_panels) return;
+  const uint32_t panel = __builtin_amdgcn_readfirstlane(panels[pslot]);
+  const int64_t row = (int64_t)panel * kPanel + (wid % WPP) * R + lane / LPR;
+  const int64_t n = (int64_t)blockIdx.y * (4 * LPR) + 4 * (lane % LPR);
+  if (row >= M) return;                    // the whole group leaves together
+  // Lanes whose columns lie past N (N is a multiple of 4: whole vectors only) stay: they hold
+  // entries that the other lanes of the group fetch from them.  They read a clamped address
+  // and store nothing.
+  const bool in_range = n < N;
+  const int32_t s = rowptr[row], t = rowptr[row + 1];
+  if (t - s > kLongRow) return;
+  const float* __restrict__ Bn = B + (in_range ? n : N - 4);
+  float4_t acc = {0.f, 0.f, 0.f, 0.f};
+  // The group fetches LPR entries of its row with one coalesced load each for column and
+  // value (lane i of the group takes entry i) and hands them out across lanes, four at a
+  // time: one B-row load per entry is then the only traffic through the vector-memory pipe.
+  const int gl = lane % LPR;               // lane inside the group
+  const int g0 = lane - gl;                // first lane of the group
+  for (int32_t e0 = s; e0 < t; e0 += LPR) {
+    const int32_t me = min(e0 + gl, t - 1);
+    const int32_t cv = colind[me];                      // past the end: the last entry again,
+    const float av = e0 + gl < t ? vals[me] : 0.f;      // with a zero multiplier
+    const int cnt = min(LPR, t - e0);
+    for (int x0 = 0; x0 < cnt; x0 += 4) {
+      float4_t b[4];
+      float a[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int src = g0 + min(x0 + x, LPR - 1);
+        const int32_t c = __shfl(cv, src, 64);
+        a[x] = __shfl(av, src, 64);
+        b[x] = *reinterpret_cast<const float4_t*>(Bn + (int64_t)c * N);
+      }
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[w] = fmaf(a[x], b[x][w], acc[w]);
+      }
+    }
+  }
+  if (in_range) __builtin_nontemporal_store(acc, reinterpret_cast<float4_t*>(C + row * N + n));
+}
+
+// One workgroup per long row: its 4 * (64/LPR) lane groups take the row's entries in turn, four
+// at a time, and their partial sums are added in group order through LDS (deterministic).
+// `long_rows` lists every row of the matrix with more than kLongRow entries; rows whose panel
+// is not in the sorted list `panels` belong to the brick kernel and are skipped.
+template <int LPR>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu_long(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
+    const float* __restrict__ vals, const uint32_t* __restrict__ long_rows,
+    const uint32_t* __restrict__ panels, int64_t n_panels, const float* __restrict__ B,
+    float* __restrict__ C, int64_t N) {
+  constexpr int R = 64 / LPR;
+  constexpr int G = R * kWavesPerBlock;    // lane groups of the workgroup
+  __shared__ float4_t part[G][LPR];
+  const int64_t row = long_rows[blockIdx.x];
+  const uint32_t panel = (uint32_t)(row / kPanel);
+  {   // is the row's panel routed here?  (uniform binary search in the sorted panel list)
+    int64_t lo = 0, hi = n_panels;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if (panels[mid] < panel) lo = mid + 1; else hi = mid;
+    }
+    if (lo >= n_panels || panels[lo] != panel) return;
+  }
+  const int lane = threadIdx.x & 63;
+  const int grp = (threadIdx.x >> 6) * R + lane / LPR;
+  const int gl = lane % LPR;
+  const int64_t n = (int64_t)blockIdx.y * (4 * LPR) + 4 * gl;
+  const bool active = n < N;
+  const int32_t s = rowptr[row], t = rowptr[row + 1];
+  const float* __restrict__ Bn = B + (active ? n : 0);
+  float4_t acc = {0.f, 0.f, 0.f, 0.f};
+  for (int32_t e = s + 4 * grp; e < t; e += 4 * G) {
+    int32_t c[4];
+    float a[4];
+    float4_t b[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int32_t ex = min(e + x, t - 1);
+      c[x] = colind[ex];
+      a[x] = e + x < t ? vals[ex] : 0.f;
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) b[x] = *reinterpret_cast<const float4_t*>(Bn + (int64_t)c[x] * N);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[w] = fmaf(a[x], b[x][w], acc[w]);
+    }
+  }
+  part[grp][gl] = acc;
+  __syncthreads();
+  if (grp == 0 && active) {
+    float4_t sum = part[0][gl];
+    for (int q = 1; q < G; ++q) sum += part[q][gl];
+    __builtin_nontemporal_store(sum, reinterpret_cast<float4_t*>(C + row * N + n));
+  }
+}
+
 // ------------------------------------------------------------------ merge (a8)
 // Sum the partial 16 x N tiles of a split panel in part order and store to C.
 // One workgroup per split panel; VEC floats per thread per step.
@@ -586,20 +710,43 @@ hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t
 }
 
 hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const float* vals,
-                            const uint32_t* panels, int64_t n_panels, const float* B, float* C,
-                            int64_t M, int64_t N, hipStream_t s) {
+                            const uint32_t* panels, int64_t n_panels, const uint32_t* long_rows,
+                            int64_t n_long_rows, const float* B, float* C, int64_t M, int64_t N,
+                            hipStream_t s) {
   if (n_panels == 0 || N == 0) return hipSuccess;
   const bool a16 = ptr_aligned16(B) && ptr_aligned16(C);
-  const unsigned gx = (unsigned)((n_panels * kPanel + kWavesPerBlock - 1) / kWavesPerBlock);
-  auto go = [&](auto kernel, int V) {
-    const unsigned gy = (unsigned)((N + 64 * V - 1) / (64 * V));
-    hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3(64 * kWavesPerBlock), 0, s, rowptr, colind, vals,
-                       panels, n_panels, B, C, M, N);
+  if (a16 && N % 4 == 0) {
+    // lanes per row: the smallest power of two that covers N in vectors of four, at most 64
+    int lpr = 4;
+    while (lpr < 64 && 4 * lpr < N) lpr *= 2;
+    const unsigned gy = (unsigned)((N + 4 * lpr - 1) / (4 * lpr));
+    const int wpp = kPanel / (64 / lpr);
+    const unsigned gx = (unsigned)((n_panels * wpp + kWavesPerBlock - 1) / kWavesPerBlock);
+#define SPMM_LAUNCH_ROWS(L)                                                                     \
+  do {                                                                                          \
+    hipLaunchKernelGGL(k_spmm_valu_rows<L>, dim3(gx, gy), dim3(64 * kWavesPerBlock), 0, s,      \
+                       rowptr, colind, vals, panels, n_panels, B, C, M, N);                     \
+    if (n_long_rows > 0)                                                                        \
+      hipLaunchKernelGGL(k_spmm_valu_long<L>, dim3((unsigned)n_long_rows, gy),                  \
+                         dim3(64 * kWavesPerBlock), 0, s, rowptr, colind, vals, long_rows,      \
+                         panels, n_panels, B, C, N);                                            \
+  } while (0)
+    switch (lpr) {
+      case 4: SPMM_LAUNCH_ROWS(4); break;
+      case 8: SPMM_LAUNCH_ROWS(8); break;
+      case 16: SPMM_LAUNCH_ROWS(16); break;
+      case 32: SPMM_LAUNCH_ROWS(32); break;
+      default: SPMM_LAUNCH_ROWS(64); break;
+    }
+#undef SPMM_LAUNCH_ROWS
     return hipGetLastError();
-  };
-  if (a16 && N % 4 == 0 && N > 128) return go(k_spmm_valu<4, true>, 4);
-  if (a16 && N % 2 == 0 && N > 64) return go(k_spmm_valu<2, true>, 2);
-  return go(k_spmm_valu<1, true>, 1);
+  }
+  // any N, any alignment: one wavefront per row
+  const unsigned gx = (unsigned)((n_panels * kPanel + kWavesPerBlock - 1) / kWavesPerBlock);
+  const unsigned gy = (unsigned)((N + 63) / 64);
+  hipLaunchKernelGGL((k_spmm_valu<1, true>), dim3(gx, gy), dim3(64 * kWavesPerBlock), 0, s, rowptr,
+                     colind, vals, panels, n_panels, B, C, M, N);
+  return hipGetLastError();
 }
 
 hipError_t launch_merge(const MergeItem* items, int64_t n_items, const float* partial, float* C,

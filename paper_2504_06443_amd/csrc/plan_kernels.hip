@@ -259,6 +259,15 @@ __global__ void k_count_flags(const uint8_t* __restrict__ flags, int64_t n,
   if (threadIdx.x == 0 && total) atomicAdd(counter, (unsigned long long)total);
 }
 
+// Rows with more than `threshold` entries, compacted in any order (the CSR kernel gives each of
+// them a workgroup of its own).  The list has room for nnz / threshold + 1 rows.
+__global__ void k_find_long_rows(const int32_t* __restrict__ rowptr, int64_t M, int threshold,
+                                 uint32_t* __restrict__ list, unsigned long long* counter) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= M) return;
+  if (rowptr[i + 1] - rowptr[i] > threshold) list[atomicAdd(counter, 1ull)] = (uint32_t)i;
+}
+
 // ---------------------------------------------------------------- scan
 // Three-pass exclusive scan (block sums, scan of block sums, rescan + offset).
 constexpr int kScanThreads = 256;
@@ -965,6 +974,14 @@ hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long lon
   if (n == 0) return hipSuccess;
   const unsigned g = (unsigned)std::min<int64_t>(grid_for(n), 2048);
   hipLaunchKernelGGL(k_count_flags, dim3(g), dim3(kThreads), 0, s, flags, n, counter);
+  return hipGetLastError();
+}
+
+hipError_t launch_find_long_rows(const int32_t* rowptr, int64_t M, int threshold, uint32_t* list,
+                                 unsigned long long* counter, hipStream_t s) {
+  if (M == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_find_long_rows, dim3(grid_for(M)), dim3(kThreads), 0, s, rowptr, M,
+                     threshold, list, counter);
   return hipGetLastError();
 }
 

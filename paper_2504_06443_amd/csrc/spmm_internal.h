@@ -27,7 +27,8 @@ enum : int {
   kCntNonEmptyPanels = 9,
   kCntDistinctCols = 10,
   kCntPopHist = 11,         // 65
-  kNumCounters = 76
+  kCntLongRows = 76,        // rows with more entries than the CSR kernel handles side by side
+  kNumCounters = 77
 };
 
 struct WorkItem {           // one wavefront's share of the MFMA kernel
@@ -78,6 +79,9 @@ hipError_t launch_brick_hist(const uint64_t* brick_mask, int64_t nb, unsigned lo
                              hipStream_t s);
 hipError_t launch_count_flags(const uint8_t* flags, int64_t n, unsigned long long* counter,
                               hipStream_t s);
+// rows with more than `threshold` entries -> list (any order), count added to *counter
+hipError_t launch_find_long_rows(const int32_t* rowptr, int64_t M, int threshold,
+                                 uint32_t* list, unsigned long long* counter, hipStream_t s);
 
 // per-panel path (LDS bitmap over the panel's column span)
 // out[0] = widest column span of a panel, out[1] = most entries of a panel
@@ -142,9 +146,13 @@ int bf16_resident_waves_per_cu(int64_t N, int planes);
 hipError_t launch_spmm_bf16(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
                             int64_t K, int planes, int64_t nnz, hipStream_t s);
+// `panels` is sorted ascending; `long_rows` lists the rows of the whole matrix with more than
+// long_row_threshold() entries (any order)
+int long_row_threshold();
 hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const float* vals,
-                            const uint32_t* panels, int64_t n_panels, const float* B, float* C,
-                            int64_t M, int64_t N, hipStream_t s);
+                            const uint32_t* panels, int64_t n_panels, const uint32_t* long_rows,
+                            int64_t n_long_rows, const float* B, float* C, int64_t M, int64_t N,
+                            hipStream_t s);
 hipError_t launch_merge(const MergeItem* items, int64_t n_items, const float* partial, float* C,
                         int64_t M, int64_t N, hipStream_t s);
 

@@ -125,6 +125,33 @@ def test_integer_values_are_exact(gpu, N):
             assert np.array_equal(Cg.astype(np.float64), Cref), (route, split)
 
 
+@pytest.mark.parametrize("N", [4, 16, 32, 64, 100, 128, 256, 300, 512, 520, 1024, 6])
+def test_csr_kernel_rows_side_by_side_and_long_rows(gpu, N):
+    """The CSR path puts several rows into one wavefront (64 / lanes-per-row of them) and gives
+    rows above 256 entries a workgroup of their own: rows of 0, 1, 255, 256, 257, 1000 and 2999
+    entries next to ordinary ones, a ragged last panel, at widths on both sides of every
+    lanes-per-row step; also under the class routing, where only Low-synergy panels go there."""
+    rng = np.random.default_rng(4)
+    M, K = 203, 3000
+    lens = rng.integers(0, 40, size=M)
+    lens[[3, 17, 18, 50, 64, 130, 202]] = [255, 256, 257, 1000, 2999, 1, 0]
+    rows = np.repeat(np.arange(M), lens)
+    cols = np.concatenate([rng.choice(K, size=l, replace=False) for l in lens])
+    A = W.csr_from_coo(M, K, rows, cols, rng.uniform(-1, 1, size=rows.size).astype(np.float32))
+    assert np.array_equal(np.diff(A.rowptr), lens)
+    B = W.dense_b(K, N, 8)
+    Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+    plan = make_plan(gpu, A)
+    for route in (gpu.ROUTE_VALU, gpu.ROUTE_CLASS):
+        print(f"csr rows case N={N} route={route}", flush=True)
+        Cg = run_product(gpu, plan, A, B, route=route)
+        assert not np.isnan(Cg).any(), "every element of C must be written"
+        check_c(Cg, Cref, S)
+    C1 = run_product(gpu, plan, A, B, route=gpu.ROUTE_VALU)
+    C2 = run_product(gpu, plan, A, B, route=gpu.ROUTE_VALU)
+    assert np.array_equal(C1, C2), "the long-row reduction must be reproducible"
+
+
 def test_identity_and_permutation(gpu):
     n, N = 1000, 64
     B = W.dense_b(n, N, 3)
@@ -371,6 +398,36 @@ def test_exec_on_side_stream_and_graph_replay(gpu):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(Cs, expect), f"replay {k}"
+
+
+def test_auto_routing_sends_low_synergy_panels_to_csr_only_at_narrow_widths(gpu):
+    """The automatic policy: brick kernel everywhere, except panels of Low synergy (Table 1:
+    fewer than 8 stored elements per brick on average) when N <= 32.  The expected panel sets
+    come from the oracle's format; the product is checked at both kinds of width."""
+    top = W.clustered_blocks(1536, 6, 90, seed=50)                     # Medium panels
+    low = W.power_law(M=1500, target_nnz=None, cap=300, seed=51)        # Low panels, some empty
+    rows = np.concatenate([np.repeat(np.arange(top.M), np.diff(top.rowptr)),
+                           top.M + np.repeat(np.arange(low.M), np.diff(low.rowptr))])
+    A = W.csr_from_coo(top.M + low.M, max(top.K, low.K), rows,
+                       np.concatenate([top.colind, low.colind]), np.concatenate([top.vals, low.vals]))
+    ref = oracle.build_bricks(A.M, A.rowptr, A.colind, A.vals)
+    P = len(ref["panel_ptr"]) - 1
+    nb_p = np.diff(ref["panel_ptr"].astype(np.int64))
+    nnz_p = np.diff(A.rowptr[np.minimum(np.arange(P + 1) * 16, A.M)].astype(np.int64))
+    low_panels = np.nonzero((nb_p > 0) & (nnz_p < 8 * nb_p))[0]
+    empty_panels = np.nonzero(nb_p == 0)[0]
+    assert len(low_panels) > 10 and (nnz_p[nb_p > 0] >= 8 * nb_p[nb_p > 0]).sum() > 10
+    plan = make_plan(gpu, A)
+    gpu.spmm_plan_set_route(plan, gpu.ROUTE_AUTO)
+    for N in (16, 32):
+        wl = gpu.spmm_plan_worklist(plan, N)
+        assert sorted(wl["valu_panels"].tolist()) == sorted(low_panels.tolist() + empty_panels.tolist()), N
+    for N in (33, 64, 128, 512):
+        assert gpu.spmm_plan_worklist(plan, N)["n_valu_panels"] == 0, N
+    for N in (32, 64):
+        B = W.dense_b(A.K, N, 3)
+        Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
+        check_c(run_product(gpu, plan, A, B, route=gpu.ROUTE_AUTO), Cref, S)
 
 
 def test_error_paths_on_device(gpu):
