@@ -152,6 +152,49 @@ def synergy(M, K, N, rowptr, colind, fmt: dict) -> dict:
 
 
 # ---------------------------------------------------------------------------
+# Section 4, Eq. 5: 32-row panels with up to two bricks per brick column
+# ---------------------------------------------------------------------------
+def build_tm32(M, rowptr, colind, vals, num: int = 6, den: int = 5) -> dict:
+    """CSR -> 32-row panel format.  The two 16-row halves of a super-panel share one
+    left-packed column list where |union| * den < num * max(|top|, |bottom|); elsewhere they
+    keep their own lists (the bricks of the 16-row format).  Returns the arrays described in
+    spmm_oracle.c plus the counts Q, nbc, nbr, n_merged and beta = nbr / nbc (Eq. 5)."""
+    rowptr, colind, vals = _i32(rowptr), _i32(colind), _f32(vals)
+    sizes = np.zeros(4, dtype=np.int64)
+    _L().oracle_tm32_sizes(C.c_int64(M), _p(rowptr), _p(colind), C.c_int64(num), C.c_int64(den),
+                           _p(sizes))
+    Q, nbc, nbr, merged = (int(x) for x in sizes)
+    nnz = int(rowptr[M])
+    out = dict(
+        sp_ptr=np.zeros(Q + 1, dtype=np.uint32),
+        sp_merged=np.zeros(Q, dtype=np.uint8),
+        bc_cols=np.zeros(4 * nbc, dtype=np.uint32),
+        bc_brick=np.zeros(nbc + 1, dtype=np.uint32),
+        br_row=np.zeros(nbr, dtype=np.uint8),
+        br_mask=np.zeros(nbr, dtype=np.uint64),
+        br_valptr=np.zeros(nbr + 1, dtype=np.uint32),
+        vals=np.zeros(nnz, dtype=np.float32),
+    )
+    _L().oracle_tm32_build(C.c_int64(M), _p(rowptr), _p(colind), _p(vals), C.c_int64(num),
+                           C.c_int64(den), _p(out["sp_ptr"]), _p(out["sp_merged"]),
+                           _p(out["bc_cols"]), _p(out["bc_brick"]), _p(out["br_row"]),
+                           _p(out["br_mask"]), _p(out["br_valptr"]), _p(out["vals"]))
+    out.update(Q=Q, nbc=nbc, nbr=nbr, n_merged=merged, beta=(nbr / nbc if nbc else 0.0))
+    return out
+
+
+def tm32_to_csr(M, fmt: dict):
+    nnz = int(fmt["br_valptr"][-1])
+    rowptr = np.zeros(M + 1, dtype=np.int32)
+    colind = np.zeros(nnz, dtype=np.int32)
+    vals = np.zeros(nnz, dtype=np.float32)
+    _L().oracle_tm32_to_csr(C.c_int64(M), _p(fmt["sp_ptr"]), _p(fmt["bc_cols"]),
+                            _p(fmt["bc_brick"]), _p(fmt["br_row"]), _p(fmt["br_mask"]),
+                            _p(fmt["br_valptr"]), _p(fmt["vals"]), _p(rowptr), _p(colind), _p(vals))
+    return rowptr, colind, vals
+
+
+# ---------------------------------------------------------------------------
 # Section 5, Eq. 6-7: wave-aware split of heavy row panels along K
 # ---------------------------------------------------------------------------
 def _ceil_div(a: int, b: int) -> int:

@@ -25,7 +25,7 @@ import numpy as np
 __all__ = [
     "CSR", "csr_from_coo", "dense_b",
     "tiny_banded", "clustered_blocks", "power_law", "brick_sweep",
-    "uniform_random", "config", "CONFIG_NAMES",
+    "uniform_random", "paired_panels", "config", "CONFIG_NAMES",
 ]
 
 
@@ -193,6 +193,44 @@ def brick_sweep(fill: float, M: int = 65536, target_nnz: int = 2_000_000,
     rr = gr[:, None] * brick_m + pick // brick_k
     cc = gc[:, None] * brick_k + pick % brick_k
     csr = csr_from_coo(M, K, rr.ravel(), cc.ravel())
+    return _fill_uniform(csr, rng)
+
+
+# --------------------------------------------------------------------------
+# consecutive 16-row panels with (nearly) common active columns
+# --------------------------------------------------------------------------
+def paired_panels(M: int, cols_per_group: int = 240, half_width: int = 1024, row_fill: float = 0.19,
+                  group_rows: int = 32, seed: int = 1006, chunk_groups: int = 2048) -> CSR:
+    """Rows are grouped `group_rows` at a time.  Each group draws `cols_per_group` distinct
+    columns within `half_width` of the diagonal, and every row of the group stores each of
+    them with probability `row_fill`.  With 32-row groups both 16-row halves of a group see
+    almost the same active columns (the first of the two extreme non-zero distributions of
+    Section 4's discussion of the row-panel height), at a column density of about
+    `row_fill`; values U(-1,1)."""
+    rng = np.random.default_rng(seed)
+    K = M
+    ngroups = -(-M // group_rows)
+    width = 2 * half_width + 1
+    all_rows, all_cols = [], []
+    for g0 in range(0, ngroups, chunk_groups):
+        g1 = min(ngroups, g0 + chunk_groups)
+        n = g1 - g0
+        centre = (np.arange(g0, g1) * group_rows + group_rows // 2)
+        keys = rng.random((n, width), dtype=np.float32)
+        cand = centre[:, None] + np.arange(-half_width, half_width + 1)[None, :]
+        keys[(cand < 0) | (cand >= K)] = np.inf
+        pick = np.argpartition(keys, cols_per_group - 1, axis=1)[:, :cols_per_group]
+        ok = np.isfinite(np.take_along_axis(keys, pick, axis=1))
+        cols = np.take_along_axis(cand, pick, axis=1)                      # [n, cols_per_group]
+        store = rng.random((n, group_rows, cols_per_group), dtype=np.float32) < row_fill
+        store &= ok[:, None, :]
+        rows = (np.arange(g0, g1) * group_rows)[:, None, None] + np.arange(group_rows)[None, :, None]
+        store &= rows < M
+        rr = np.broadcast_to(rows, store.shape)[store]
+        cc = np.broadcast_to(cols[:, None, :], store.shape)[store]
+        all_rows.append(rr)
+        all_cols.append(cc)
+    csr = csr_from_coo(M, K, np.concatenate(all_rows), np.concatenate(all_cols))
     return _fill_uniform(csr, rng)
 
 
