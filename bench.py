@@ -54,6 +54,10 @@ def make_workload(name):
     if name.startswith("sweepxl_"):            # scaled-up sweep: exceeds the 256 MB Infinity Cache
         fill = float(name.split("_f")[1])
         return W.brick_sweep(fill, M=1 << 20, target_nnz=32_000_000, seed=1005), 128
+    if name.startswith("paired_"):             # 32-row groups with common active columns
+        rows = {"262k": 262144, "923k": 923136}[name.split("_")[1]]
+        return W.paired_panels(rows, cols_per_group=240, half_width=1024, row_fill=0.19,
+                               seed=1006), 128
     idx, kw, n = WORKLOADS[name]
     A, _ = W.config(idx, **kw)
     return A, n
@@ -110,7 +114,7 @@ def cpu_baseline(A, B, budget_s=20.0):
 
 
 def measure(spmm, name, N, steps, warmup, route="auto", split=0, order="panel", cold=False,
-            mode="fp32", time_plan=True, keep=None):
+            mode="fp32", time_plan=True, keep=None, panel_height=16):
     """Plans `name`, runs warmup + steps products and returns the measurements as a dict.
     `keep`, if a dict, receives A and the first B (for the cpu_baseline leg)."""
     import numpy as np
@@ -143,6 +147,10 @@ def measure(spmm, name, N, steps, warmup, route="auto", split=0, order="panel", 
     spmm.spmm_plan_set_order(plan, 1 if order == "heavy" else 0)
     if mode != "fp32":
         spmm.spmm_plan_set_precision(plan, spmm.PRECISIONS[mode])
+    tm32 = None
+    if panel_height == 32:
+        spmm.spmm_plan_set_panel_height(plan, 32)
+        tm32 = spmm.spmm_plan_tm32_sizes(plan)
     syn = spmm.spmm_synergy(plan, N)
     wl = spmm.spmm_plan_worklist(plan, N)
 
@@ -179,7 +187,8 @@ def measure(spmm, name, N, steps, warmup, route="auto", split=0, order="panel", 
     flops = 2.0 * A.nnz * N
     # algorithmic work of the dominant kernel (the MFMA brick kernel unless everything is
     # routed to the CSR kernel): issued flops = 128 flop per brick and column of C
-    issued_flops = 128.0 * sum(b1 - b0 for _, b0, b1, _, _ in wl["items"]) * N
+    issued_flops = 128.0 * (tm32["n_bricks"] if tm32 else
+                            sum(b1 - b0 for _, b0, b1, _, _ in wl["items"])) * N
     hbm_achieved = syn["bytes_min"] / (kernel_ms * 1e-3) / 1e9
     mfma_achieved = issued_flops / (kernel_ms * 1e-3) / 1e12
     traffic = stored_traffic(name, N, mode) if (route == "auto" and split == 0) else None
@@ -213,6 +222,7 @@ def measure(spmm, name, N, steps, warmup, route="auto", split=0, order="panel", 
         "worklist": {k: wl[k] for k in ("n_mfma_items", "n_valu_panels", "n_split_panels",
                                         "num_waves", "n_tile", "n_tiles", "num_cus",
                                         "resident_waves_per_cu")},
+        "tm32": tm32,
         "roofline": roof_mfma if mfma_binds else roof_hbm,
         "roofline_hbm": roof_hbm,
         "roofline_mfma": roof_mfma,
@@ -253,6 +263,9 @@ def main():
     ap.add_argument("--mode", default="fp32", choices=["fp32", "bf16x3", "bf16x6"],
                     help="arithmetic of the brick kernel: fp32 (default), or the opt-in split-bf16 "
                          "modes (three / six bf16 products per FP32 product)")
+    ap.add_argument("--panel-height", type=int, default=16, choices=[16, 32],
+                    help="32: build and use the 32-row panel format (two bricks per brick column "
+                         "share one B operand)")
     ap.add_argument("--cold", action="store_true",
                     help="rotate over several B/C pairs so that no step finds its operands in cache")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -296,7 +309,8 @@ def main():
 
     keep = {}
     r = measure(spmm, args.workload, args.n, args.steps, args.warmup, route=args.route,
-                split=args.split, order=args.order, cold=args.cold, mode=args.mode, keep=keep)
+                split=args.split, order=args.order, cold=args.cold, mode=args.mode, keep=keep,
+                panel_height=args.panel_height)
     out = {
         "metric": "SpMM effective GFLOP/s (2*nnz*N/t)",
         "value": r["value"],
@@ -312,9 +326,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "M": r["M"], "K": r["K"], "nnz": r["nnz"], "N": r["N"],
                    "route": args.route, "split": args.split, "order": args.order,
-                   "mode": args.mode, "cold": bool(args.cold), "bc_pairs": r["bc_pairs"]},
+                   "mode": args.mode, "panel_height": args.panel_height, "cold": bool(args.cold),
+                   "bc_pairs": r["bc_pairs"]},
     }
-    for k in ("kernel_ms_mean", "kernel_ms_median", "plan_ms", "plan_first_ms", "synergy", "worklist",
+    for k in ("kernel_ms_mean", "kernel_ms_median", "plan_ms", "plan_first_ms", "synergy", "worklist", "tm32",
               "roofline", "roofline_hbm", "roofline_mfma"):
         out[k] = r[k]
     out["achieved_hbm_gbs_model"] = r["roofline_hbm"]["achieved"]
@@ -323,7 +338,7 @@ def main():
     keep.clear()
     default_run = (args.workload == DEFAULT_WORKLOAD and args.n == 0 and args.route == "auto"
                    and args.split == 0 and args.order == "panel" and args.mode == "fp32"
-                   and not args.cold)
+                   and args.panel_height == 16 and not args.cold)
     if default_run and not args.no_extra:
         extra = {}
         for name in EXTRA_WORKLOADS:

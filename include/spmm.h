@@ -234,6 +234,40 @@ int spmm_plan_set_order(spmm_plan_t *plan, int order);
 enum spmm_precision { SPMM_PRECISION_FP32 = 0, SPMM_PRECISION_BF16X3 = 1, SPMM_PRECISION_BF16X6 = 2 };
 int spmm_plan_set_precision(spmm_plan_t *plan, int precision);
 
+/* ---------------------------------------------------------------------------
+ * Row panels of 32 rows (Section 4, Eq. 5).  With TM = 32 a brick column holds up to two
+ * 16x4 bricks (rows 0..15 and rows 16..31 of the super-panel) and the B rows loaded for it
+ * serve both: beta = bricks per brick column.  The paper always ran TM = 16 and gives no rule
+ * for when 32 pays; here the two halves of a super-panel share one left-packed column list
+ * only where |cols(top) U cols(bottom)| * merge_den < merge_num * max(|cols(top)|,
+ * |cols(bottom)|) (6/5 is a sensible choice; 0/1 never merges), and keep their own lists
+ * elsewhere, so that unrelated halves do not dilute each other's bricks.
+ *
+ * spmm_plan_set_panel_height(plan, 32, num, den, stream) builds that format on the GPU from
+ * the 16-row one (synchronises `stream`, allocates) and makes spmm_exec use the 32-row kernel
+ * whenever every panel is routed to the MFMA kernel (SPMM_ROUTE_AUTO / _MFMA), the arithmetic
+ * is FP32, N is a multiple of 4 (of the vector width below 64), B and C are 16-byte aligned
+ * and B is below 4 GiB; other calls use the 16-row path.  Heavy panels are not split along K
+ * in this mode.  Height 16 switches back (the 32-row arrays are kept).
+ *
+ * 32-row format (Q = ceil(P/2) super-panels, nbc brick columns, nbr bricks):
+ *   sp_ptr u32[Q+1]     first brick column of each super-panel
+ *   sp_merged u8[Q]     1 where the halves share a column list
+ *   bc_cols u32[4 nbc]  column ids (ascending per list, pad 0xFFFFFFFF)
+ *   bc_brick u32[nbc+1] first brick of each brick column (one or two bricks: top first)
+ *   br_row u8[nbr]      0 = rows 0..15, 1 = rows 16..31 of the super-panel
+ *   br_mask u64[nbr], br_valptr u32[nbr+1], vals f32[nnz]  as in the 16-row format
+ */
+typedef struct spmm_tm32_sizes {
+  int64_t n_super_panels, n_brick_cols, n_bricks, n_merged;
+} spmm_tm32_sizes_t;
+int spmm_plan_set_panel_height(spmm_plan_t *plan, int rows, uint32_t merge_num, uint32_t merge_den,
+                               void *stream);
+int spmm_plan_tm32_sizes(const spmm_plan_t *plan, spmm_tm32_sizes_t *out /* host */);
+int spmm_plan_tm32_export(const spmm_plan_t *plan, uint32_t *sp_ptr, uint8_t *sp_merged,
+                          uint32_t *bc_cols, uint32_t *bc_brick, uint8_t *br_row, uint64_t *br_mask,
+                          uint32_t *br_valptr, float *vals /* all host, sized by the above */);
+
 /* Host-only arithmetic of Eq. 6-7; needs no GPU.
  *   n_panels, nbricks[n_panels]  bricks per panel (a block is 4 bricks)
  *   work_items   thread-block count before splitting ("Total_thread_blocks")

@@ -37,6 +37,7 @@ EXPORTED = (
     "spmm_plan_sizes",
     "spmm_plan_export",
     "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_plan_set_precision",
+    "spmm_plan_set_panel_height", "spmm_plan_tm32_sizes", "spmm_plan_tm32_export",
     "spmm_partition_counts",
     "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error",
 )
@@ -68,6 +69,11 @@ class _Sizes(C.Structure):
                 ("n_panels", C.c_int64), ("n_bricks", C.c_int64)]
 
 
+class _Tm32Sizes(C.Structure):
+    _fields_ = [("n_super_panels", C.c_int64), ("n_brick_cols", C.c_int64),
+                ("n_bricks", C.c_int64), ("n_merged", C.c_int64)]
+
+
 class _WorkItem(C.Structure):
     _fields_ = [("panel", C.c_uint32), ("brick_begin", C.c_uint32), ("brick_end", C.c_uint32),
                 ("part", C.c_uint32), ("nparts", C.c_uint32)]
@@ -93,6 +99,9 @@ _lib.spmm_plan_set_route.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_split.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_order.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_precision.argtypes = [_vp, C.c_int]
+_lib.spmm_plan_set_panel_height.argtypes = [_vp, C.c_int, C.c_uint32, C.c_uint32, _vp]
+_lib.spmm_plan_tm32_sizes.argtypes = [_vp, C.POINTER(_Tm32Sizes)]
+_lib.spmm_plan_tm32_export.argtypes = [_vp] + [_vp] * 8
 _lib.spmm_partition_counts.argtypes = [C.c_int64, _vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                        _vp, C.POINTER(C.c_int64)]
 _lib.spmm_plan_worklist.argtypes = [_vp, C.c_int64, C.POINTER(_WorklistInfo), _vp, _vp]
@@ -229,6 +238,35 @@ def spmm_plan_set_order(plan: Plan, order: int):
 
 def spmm_plan_set_precision(plan: Plan, precision: int):
     _check(_lib.spmm_plan_set_precision(plan._h, precision))
+
+
+def spmm_plan_set_panel_height(plan: Plan, rows: int, merge_num: int = 6, merge_den: int = 5,
+                               stream=None):
+    """rows = 32: build the 32-row panel format and use it where it applies; 16: back."""
+    _check(_lib.spmm_plan_set_panel_height(plan._h, rows, merge_num, merge_den, _stream_ptr(stream)))
+
+
+def spmm_plan_tm32_sizes(plan: Plan) -> dict:
+    s = _Tm32Sizes()
+    _check(_lib.spmm_plan_tm32_sizes(plan._h, C.byref(s)))
+    return {n: getattr(s, n) for n, _ in _Tm32Sizes._fields_}
+
+
+def spmm_plan_tm32_export(plan: Plan) -> dict:
+    """Copy the 32-row panel format to host numpy arrays."""
+    sz = spmm_plan_tm32_sizes(plan)
+    Q, nbc, nbr = sz["n_super_panels"], sz["n_brick_cols"], sz["n_bricks"]
+    out = dict(
+        sp_ptr=np.zeros(Q + 1, dtype=np.uint32), sp_merged=np.zeros(Q, dtype=np.uint8),
+        bc_cols=np.zeros(4 * nbc, dtype=np.uint32), bc_brick=np.zeros(nbc + 1, dtype=np.uint32),
+        br_row=np.zeros(nbr, dtype=np.uint8), br_mask=np.zeros(nbr, dtype=np.uint64),
+        br_valptr=np.zeros(nbr + 1, dtype=np.uint32), vals=np.zeros(plan.nnz, dtype=np.float32),
+    )
+    _check(_lib.spmm_plan_tm32_export(plan._h, *[out[k].ctypes.data_as(_vp) for k in
+                                                 ("sp_ptr", "sp_merged", "bc_cols", "bc_brick",
+                                                  "br_row", "br_mask", "br_valptr", "vals")]))
+    out.update(sz)
+    return out
 
 
 def spmm_partition_counts(nbricks, work_items: int, num_cus: int, resident_per_cu: int,

@@ -100,6 +100,25 @@ struct spmm_plan {
   int split = 0;
   int order = SPMM_ORDER_PANEL;
   int precision = SPMM_PRECISION_FP32;
+  // 32-row panel format (built on request; Section 4, Eq. 5)
+  int panel_height = 16;
+  struct Tm32 {
+    int64_t Q = 0, nbc = 0, nbr = 0, n_merged = 0;
+    char* arena = nullptr;        // everything below, one allocation
+    uint32_t* sp_ptr = nullptr;
+    uint8_t* sp_merged = nullptr;
+    uint32_t* bc_cols = nullptr;
+    uint32_t* bc_brick = nullptr;
+    uint8_t* br_row = nullptr;
+    uint64_t* br_mask = nullptr;
+    uint32_t* br_valptr = nullptr;
+    float* vals = nullptr;
+    Tm32Meta* meta = nullptr;
+    // kept for value-only updates: where the entries of the 16-row format went
+    uint32_t* new_slot = nullptr;
+    uint8_t* brick_half = nullptr;
+    uint32_t* pos = nullptr;
+  } tm32;
   std::map<int64_t, HostList*> host_lists;
   std::map<int64_t, WorkList*> lists;
 
@@ -116,6 +135,7 @@ struct spmm_plan {
     drop_lists();
     if (fixed_arena) (void)hipFree(fixed_arena);
     if (brick_arena) (void)hipFree(brick_arena);
+    if (tm32.arena) (void)hipFree(tm32.arena);
   }
 };
 
@@ -333,6 +353,105 @@ done:
     return status;
   }
   *out = wl;
+  return SPMM_OK;
+}
+
+// Builds the 32-row panel format from the 16-row one (device kernels; two size read-backs).
+int build_tm32(spmm_plan_t* pl, uint32_t num, uint32_t den, hipStream_t s) {
+  int status = SPMM_OK;
+  auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
+  const int64_t P = pl->P, Q = (P + 1) / 2, nb = pl->nb, nnz = pl->nnz;
+  Arena t1, t2, keep;
+  uint32_t *cpre, *nbc_q, *sp_ptr_tmp, *scan_tmp, *pos_tmp, *new_slot_tmp, *bc_cols_tmp;
+  uint8_t *merged_tmp, *half_tmp;
+  unsigned long long* tmask;
+  uint32_t h_nbc = 0, h_nbr = 0;
+  int64_t nbc = 0, nbr = 0, n_meta = 0;
+  spmm_plan::Tm32 f;
+  std::vector<uint8_t> h_merged;
+
+  t1.cap = need(4 * nb + P + 1, 4) + need(Q, 4) + need(Q + 1, 4) + need(Q, 1) + need(4 * nb, 4) +
+           need(nb, 1) + need((int64_t)scan_tmp_elems(std::max<int64_t>(2 * 4 * nb + 2, Q + 1)), 4);
+  HIP_TRY(hipMalloc((void**)&t1.base, t1.cap));
+  cpre = t1.take<uint32_t>(4 * nb + P + 1);
+  nbc_q = t1.take<uint32_t>(Q);
+  sp_ptr_tmp = t1.take<uint32_t>(Q + 1);
+  merged_tmp = t1.take<uint8_t>(Q);
+  new_slot_tmp = t1.take<uint32_t>(4 * nb);
+  half_tmp = t1.take<uint8_t>(nb);
+  scan_tmp = t1.take<uint32_t>((int64_t)scan_tmp_elems(std::max<int64_t>(2 * 4 * nb + 2, Q + 1)));
+
+  HIP_TRY(launch_tm32_count(pl->panel_ptr, pl->brick_cols, P, Q, num, den, cpre, merged_tmp, nbc_q, s));
+  HIP_TRY(launch_scan_u32(nbc_q, Q, sp_ptr_tmp, scan_tmp, s));
+  HIP_TRY(hipMemcpyAsync(&h_nbc, sp_ptr_tmp + Q, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  nbc = h_nbc;   // at most the bricks of the 16-row format
+
+  t2.cap = need((nbc + kFormatPad) * kBrickK, 4) + need(2 * nbc, 8) + need(2 * nbc + 1, 4);
+  HIP_TRY(hipMalloc((void**)&t2.base, t2.cap));
+  bc_cols_tmp = t2.take<uint32_t>((nbc + kFormatPad) * kBrickK);
+  tmask = t2.take<unsigned long long>(2 * nbc);
+  pos_tmp = t2.take<uint32_t>(2 * nbc + 1);
+  HIP_TRY(hipMemsetAsync(tmask, 0, (size_t)std::max<int64_t>(2 * nbc, 1) * 8, s));
+  HIP_TRY(hipMemsetAsync(bc_cols_tmp + nbc * kBrickK, 0, kFormatPad * kBrickK * 4, s));
+  HIP_TRY(launch_tm32_cols_masks(pl->panel_ptr, pl->brick_cols, pl->brick_mask, P, Q, nb, cpre,
+                                 merged_tmp, sp_ptr_tmp, bc_cols_tmp, new_slot_tmp, half_tmp, tmask,
+                                 s));
+  HIP_TRY(launch_scan_nonzero64(reinterpret_cast<const uint64_t*>(tmask), 2 * nbc, pos_tmp, scan_tmp, s));
+  HIP_TRY(hipMemcpyAsync(&h_nbr, pos_tmp + 2 * nbc, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  try { h_merged.resize((size_t)std::max<int64_t>(Q, 1)); }
+  catch (const std::bad_alloc&) { status = fail(SPMM_ENOMEM, "host allocation failed"); goto done; }
+  if (Q > 0)
+    HIP_TRY(hipMemcpyAsync(h_merged.data(), merged_tmp, (size_t)Q, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  nbr = h_nbr;
+  n_meta = nbc + kFormatPad;
+
+  keep.cap = need(Q + 1, 4) + need(Q, 1) + need((nbc + kFormatPad) * kBrickK, 4) + need(nbc + 1, 4) +
+             need(nbr, 1) + need(nbr, 8) + need(nbr + 1, 4) + need(nnz + 64, 4) +
+             need(n_meta, sizeof(Tm32Meta)) + need(4 * nb, 4) + need(nb, 1) + need(2 * nbc + 1, 4);
+  HIP_TRY(hipMalloc((void**)&keep.base, keep.cap));
+  f.arena = keep.base;
+  f.Q = Q; f.nbc = nbc; f.nbr = nbr;
+  for (int64_t q = 0; q < Q; ++q) f.n_merged += h_merged[q];
+  f.sp_ptr = keep.take<uint32_t>(Q + 1);
+  f.sp_merged = keep.take<uint8_t>(Q);
+  f.bc_cols = keep.take<uint32_t>((nbc + kFormatPad) * kBrickK);
+  f.bc_brick = keep.take<uint32_t>(nbc + 1);
+  f.br_row = keep.take<uint8_t>(nbr);
+  f.br_mask = keep.take<uint64_t>(nbr);
+  f.br_valptr = keep.take<uint32_t>(nbr + 1);
+  f.vals = keep.take<float>(nnz + 64);
+  f.meta = keep.take<Tm32Meta>(n_meta);
+  f.new_slot = keep.take<uint32_t>(4 * nb);
+  f.brick_half = keep.take<uint8_t>(nb);
+  f.pos = keep.take<uint32_t>(2 * nbc + 1);
+  HIP_TRY(hipMemcpyAsync(f.sp_ptr, sp_ptr_tmp, (size_t)(Q + 1) * 4, hipMemcpyDeviceToDevice, s));
+  if (Q > 0) HIP_TRY(hipMemcpyAsync(f.sp_merged, merged_tmp, (size_t)Q, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync(f.bc_cols, bc_cols_tmp, (size_t)(nbc + kFormatPad) * kBrickK * 4,
+                         hipMemcpyDeviceToDevice, s));
+  if (nb > 0) {
+    HIP_TRY(hipMemcpyAsync(f.new_slot, new_slot_tmp, (size_t)nb * kBrickK * 4, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(hipMemcpyAsync(f.brick_half, half_tmp, (size_t)nb, hipMemcpyDeviceToDevice, s));
+  }
+  HIP_TRY(hipMemcpyAsync(f.pos, pos_tmp, (size_t)(2 * nbc + 1) * 4, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(launch_tm32_compact(tmask, f.pos, nbc, f.bc_brick, f.br_row, f.br_mask, s));
+  HIP_TRY(launch_scan_popc64(f.br_mask, nbr, f.br_valptr, scan_tmp, s));
+  HIP_TRY(hipMemsetAsync(f.vals + nnz, 0, 64 * sizeof(float), s));
+  HIP_TRY(launch_tm32_values(pl->brick_mask, pl->brick_valptr, pl->vals, f.new_slot, f.brick_half,
+                             f.pos, f.br_mask, f.br_valptr, nb, f.vals, s));
+  HIP_TRY(launch_tm32_meta(f.bc_brick, f.br_row, f.br_mask, f.br_valptr, nbc, nnz, f.meta, n_meta, s));
+  HIP_TRY(hipStreamSynchronize(s));
+done:
+  if (status != SPMM_OK) (void)hipStreamSynchronize(s);
+  if (t1.base) (void)hipFree(t1.base);
+  if (t2.base) (void)hipFree(t2.base);
+  if (status != SPMM_OK) {
+    if (keep.base) (void)hipFree(keep.base);
+    return status;
+  }
+  if (pl->tm32.arena) (void)hipFree(pl->tm32.arena);
+  pl->tm32 = f;
   return SPMM_OK;
 }
 
@@ -649,6 +768,10 @@ int spmm_plan_update_values(spmm_plan_t* pl, const float* vals, void* stream_) {
   int status = SPMM_OK;
   HIP_TRY(launch_update_values(vals, pl->ent_pos, pl->nnz, pl->vals, pl->csr_vals,
                                (hipStream_t)stream_));
+  if (pl->tm32.arena)   // the 32-row format holds its own copy of the packed values
+    HIP_TRY(launch_tm32_values(pl->brick_mask, pl->brick_valptr, pl->vals, pl->tm32.new_slot,
+                               pl->tm32.brick_half, pl->tm32.pos, pl->tm32.br_mask,
+                               pl->tm32.br_valptr, pl->nb, pl->tm32.vals, (hipStream_t)stream_));
 done:
   return status;
 }
@@ -666,12 +789,27 @@ int check_exec_args(const spmm_plan_t* pl, const float* B, int64_t N, const floa
   return SPMM_OK;
 }
 
+// The 32-row kernel serves the whole matrix when the plan has that format, every panel is routed
+// to the MFMA kernel, the arithmetic is FP32 and the shape is the fast kernel's.
+bool uses_tm32(const spmm_plan_t* pl, const float* B, int64_t N, const float* C) {
+  if (pl->panel_height != 32 || !pl->tm32.arena) return false;
+  if (pl->route != SPMM_ROUTE_AUTO && pl->route != SPMM_ROUTE_MFMA) return false;
+  if (pl->precision != SPMM_PRECISION_FP32) return false;
+  return mfma_fast_shape(N, pl->K) && ptr_is_aligned16(B) && ptr_is_aligned16(C);
+}
+
 // the three launches of one product; every pointer is a device pointer
 int launch_product(const spmm_plan_t* pl, const HostList* hl, const WorkItem* d_items,
                    const uint32_t* d_valu_panels, const MergeItem* d_merge, float* d_partial,
                    const float* B, int64_t N, float* C, hipStream_t s) {
   int status = SPMM_OK;
   const BrickFormat f{pl->brick_cols, pl->brick_mask, pl->brick_valptr, pl->vals};
+  if (uses_tm32(pl, B, N, C)) {
+    // 32-row panels: one wavefront per super-panel and column tile, no work list
+    HIP_TRY(launch_spmm_tm32(pl->tm32.sp_ptr, pl->tm32.bc_cols, pl->tm32.meta, pl->tm32.vals,
+                             pl->tm32.Q, B, C, pl->M, N, pl->K, s));
+    return SPMM_OK;
+  }
   {
     const int tile = mfma_tile_for(N);
     const int V = tile >= 64 ? 4 : tile / 16;
@@ -844,6 +982,50 @@ int spmm_plan_set_precision(spmm_plan_t* pl, int precision) {
   pl->precision = precision;
   pl->drop_lists();   // the kernels differ in occupancy, which Eq. 7 uses
   return SPMM_OK;
+}
+
+int spmm_plan_set_panel_height(spmm_plan_t* pl, int rows, uint32_t merge_num, uint32_t merge_den,
+                               void* stream_) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (rows != 16 && rows != 32) return fail(SPMM_EINVAL, "panel height must be 16 or 32");
+  if (rows == 32 && merge_den == 0) return fail(SPMM_EINVAL, "merge_den is zero");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
+  if (rows == 32) {
+    const int status = build_tm32(pl, merge_num, merge_den, (hipStream_t)stream_);
+    if (status != SPMM_OK) return status;
+  }
+  pl->panel_height = rows;
+  return SPMM_OK;
+}
+
+int spmm_plan_tm32_sizes(const spmm_plan_t* pl, spmm_tm32_sizes_t* o) {
+  if (!pl || !o) return fail(SPMM_EINVAL, "NULL argument");
+  if (!pl->tm32.arena) return fail(SPMM_EINVAL, "the plan has no 32-row format");
+  o->n_super_panels = pl->tm32.Q;
+  o->n_brick_cols = pl->tm32.nbc;
+  o->n_bricks = pl->tm32.nbr;
+  o->n_merged = pl->tm32.n_merged;
+  return SPMM_OK;
+}
+
+int spmm_plan_tm32_export(const spmm_plan_t* pl, uint32_t* sp_ptr, uint8_t* sp_merged,
+                          uint32_t* bc_cols, uint32_t* bc_brick, uint8_t* br_row, uint64_t* br_mask,
+                          uint32_t* br_valptr, float* vals) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (!pl->tm32.arena) return fail(SPMM_EINVAL, "the plan has no 32-row format");
+  int status = SPMM_OK;
+  const auto& f = pl->tm32;
+  HIP_TRY(hipDeviceSynchronize());
+  if (sp_ptr) HIP_TRY(hipMemcpy(sp_ptr, f.sp_ptr, (size_t)(f.Q + 1) * 4, hipMemcpyDeviceToHost));
+  if (sp_merged && f.Q) HIP_TRY(hipMemcpy(sp_merged, f.sp_merged, (size_t)f.Q, hipMemcpyDeviceToHost));
+  if (bc_cols && f.nbc) HIP_TRY(hipMemcpy(bc_cols, f.bc_cols, (size_t)f.nbc * 16, hipMemcpyDeviceToHost));
+  if (bc_brick) HIP_TRY(hipMemcpy(bc_brick, f.bc_brick, (size_t)(f.nbc + 1) * 4, hipMemcpyDeviceToHost));
+  if (br_row && f.nbr) HIP_TRY(hipMemcpy(br_row, f.br_row, (size_t)f.nbr, hipMemcpyDeviceToHost));
+  if (br_mask && f.nbr) HIP_TRY(hipMemcpy(br_mask, f.br_mask, (size_t)f.nbr * 8, hipMemcpyDeviceToHost));
+  if (br_valptr) HIP_TRY(hipMemcpy(br_valptr, f.br_valptr, (size_t)(f.nbr + 1) * 4, hipMemcpyDeviceToHost));
+  if (vals && pl->nnz) HIP_TRY(hipMemcpy(vals, f.vals, (size_t)pl->nnz * 4, hipMemcpyDeviceToHost));
+done:
+  return status;
 }
 
 int spmm_plan_set_order(spmm_plan_t* pl, int order) {

@@ -642,21 +642,22 @@ int occupancy_fast_t() {
   return nb * kWavesPerBlock;
 }
 
+}  // namespace
+
 // the fast kernel serves N that is a multiple of the vector width with B below 4 GiB
-bool fast_path_shape(int64_t N, int64_t K) {
+bool mfma_fast_shape(int64_t N, int64_t K) {
   const int tile = mfma_tile_for(N);
   const int V = tile >= 64 ? 4 : tile / 16;
   return N % V == 0 && K > 0 && (double)K * (double)N * 4.0 < 4294967296.0;
 }
 
-}  // namespace
 
 // Wavefronts of the MFMA kernel that fit on one CU at a time, for the kernel variant that
 // (N, K) selects when the operands are 16-byte aligned: the "thread blocks per SM" of Eq. 7.
 int mfma_resident_waves_per_cu(int64_t N, int64_t K) {
   const int tile = mfma_tile_for(N);
   const int V = tile >= 64 ? 4 : tile / 16;
-  if (fast_path_shape(N, K)) {
+  if (mfma_fast_shape(N, K)) {
     switch (tile) {
       case 16: return occupancy_fast_t<1>();
       case 32: return occupancy_fast_t<2>();
@@ -681,7 +682,7 @@ hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t
   const int V = tile >= 64 ? 4 : tile / 16;
   const bool al = (N % V == 0) && ptr_aligned16(B) && ptr_aligned16(C) &&
                   (partial == nullptr || ptr_aligned16(partial));
-  if (al && fast_path_shape(N, K)) {
+  if (al && mfma_fast_shape(N, K)) {
     unsigned gx = (unsigned)((n_items + kWavesPerBlock - 1) / kWavesPerBlock);
     gx = (gx + kXcds - 1) / kXcds * kXcds;  // whole rounds over the XCDs
     const dim3 grid(gx, (unsigned)((N + tile - 1) / tile)), block(64 * kWavesPerBlock);

@@ -277,6 +277,7 @@ constexpr int kScanTile = kScanThreads * kScanItems;
 struct LoadU8 { const uint8_t* p; __device__ uint32_t operator()(int64_t i) const { return p[i]; } };
 struct LoadU32 { const uint32_t* p; __device__ uint32_t operator()(int64_t i) const { return p[i]; } };
 struct LoadPopc { const uint64_t* p; __device__ uint32_t operator()(int64_t i) const { return __popcll(p[i]); } };
+struct LoadNonZero { const uint64_t* p; __device__ uint32_t operator()(int64_t i) const { return p[i] != 0 ? 1u : 0u; } };
 
 // exclusive scan of one value per thread across the block; returns the block total
 __device__ inline uint32_t block_exclusive(uint32_t v, uint32_t* total_out) {
@@ -862,6 +863,11 @@ hipError_t launch_scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_
 hipError_t launch_scan_popc64(const uint64_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
                               hipStream_t s) {
   return scan_impl(LoadPopc{in}, n, out, tmp, s);
+}
+
+hipError_t launch_scan_nonzero64(const uint64_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
+                                 hipStream_t s) {
+  return scan_impl(LoadNonZero{in}, n, out, tmp, s);
 }
 
 hipError_t launch_validate_rowptr(const int32_t* rowptr, int64_t M, int64_t nnz, uint32_t* err,

@@ -121,6 +121,8 @@ hipError_t launch_scan_u32(const uint32_t* in, int64_t n, uint32_t* out, uint32_
                            hipStream_t s);
 hipError_t launch_scan_popc64(const uint64_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
                               hipStream_t s);
+hipError_t launch_scan_nonzero64(const uint64_t* in, int64_t n, uint32_t* out, uint32_t* tmp,
+                                 hipStream_t s);
 
 // ---- exec (a6..a8) -------------------------------------------------------
 // Device arrays of the brick format.  Each carries spare entries past its end
@@ -137,6 +139,9 @@ struct BrickFormat {
 
 int mfma_tile_for(int64_t N);   // columns of C per wavefront: 16, 32, 64 or 128
 int mfma_resident_waves_per_cu(int64_t N, int64_t K);
+// shapes the fast FP32 kernel serves when B and C are 16-byte aligned: N a multiple of the
+// vector width, B below 4 GiB
+bool mfma_fast_shape(int64_t N, int64_t K);
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
                             int64_t K, hipStream_t s);
@@ -155,5 +160,33 @@ hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const 
                             hipStream_t s);
 hipError_t launch_merge(const MergeItem* items, int64_t n_items, const float* partial, float* C,
                         int64_t M, int64_t N, hipStream_t s);
+
+// ---- 32-row panels (tm32_kernels.hip; Section 4, Eq. 5) ------------------------------------
+struct Tm32Meta {           // per brick column, for the kernel: its top and bottom brick
+  uint64_t mask_top, mask_bot;   // zero where the half has no brick in this brick column
+  uint32_t off_top, off_bot;     // start of the brick's values
+};
+hipError_t launch_tm32_count(const uint32_t* panel_ptr, const uint32_t* brick_cols, int64_t P,
+                             int64_t Q, uint32_t num, uint32_t den, uint32_t* cpre,
+                             uint8_t* sp_merged, uint32_t* nbc_q, hipStream_t s);
+hipError_t launch_tm32_cols_masks(const uint32_t* panel_ptr, const uint32_t* brick_cols,
+                                  const uint64_t* brick_mask, int64_t P, int64_t Q, int64_t nb,
+                                  const uint32_t* cpre, const uint8_t* sp_merged,
+                                  const uint32_t* sp_ptr, uint32_t* bc_cols, uint32_t* new_slot,
+                                  uint8_t* brick_half, unsigned long long* tmask, hipStream_t s);
+hipError_t launch_tm32_compact(const unsigned long long* tmask, const uint32_t* pos, int64_t nbc,
+                               uint32_t* bc_brick, uint8_t* br_row, uint64_t* br_mask,
+                               hipStream_t s);
+hipError_t launch_tm32_values(const uint64_t* brick_mask, const uint32_t* brick_valptr,
+                              const float* vals, const uint32_t* new_slot,
+                              const uint8_t* brick_half, const uint32_t* pos,
+                              const uint64_t* br_mask, const uint32_t* br_valptr, int64_t nb,
+                              float* out, hipStream_t s);
+hipError_t launch_tm32_meta(const uint32_t* bc_brick, const uint8_t* br_row, const uint64_t* br_mask,
+                            const uint32_t* br_valptr, int64_t nbc, int64_t nnz, Tm32Meta* meta,
+                            int64_t n_meta, hipStream_t s);
+hipError_t launch_spmm_tm32(const uint32_t* sp_ptr, const uint32_t* bc_cols, const Tm32Meta* meta,
+                            const float* vals, int64_t Q, const float* B, float* C, int64_t M,
+                            int64_t N, int64_t K, hipStream_t s);
 
 }  // namespace spmm
