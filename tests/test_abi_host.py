@@ -21,7 +21,7 @@ def binding():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "spmm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spmm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(spmm_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(binding):
