@@ -66,7 +66,8 @@ def make_workload(name):
 def kernel_source_hash():
     """Identifies the kernels a stored traffic figure was measured with."""
     h = hashlib.sha256()
-    for fn in ("exec_kernels.hip", "spmm_internal.h"):
+    for fn in ("exec_kernels.hip", "exec_bf16.hip", "tm32_kernels.hip", "exec_common.h",
+               "spmm_internal.h"):
         with open(os.path.join(ROOT, "paper_2504_06443_amd", "csrc", fn), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
