@@ -234,6 +234,17 @@ int spmm_plan_set_order(spmm_plan_t *plan, int order);
 enum spmm_precision { SPMM_PRECISION_FP32 = 0, SPMM_PRECISION_BF16X3 = 1, SPMM_PRECISION_BF16X6 = 2 };
 int spmm_plan_set_precision(spmm_plan_t *plan, int precision);
 
+/* Large N (Section 3.3: several thread blocks work on one row panel and share its decoded
+ * bricks).  By default every 128-column tile of a panel is an independent wavefront that
+ * fetches and decodes the panel's bricks itself.  SPMM_SHARE_WORKGROUP instead gives a panel
+ * to one workgroup of two or four wavefronts, one per tile, which decode each brick once into
+ * LDS and all read their A operands from there.  Applies to the FP32 MFMA kernel with 16-row
+ * panels when N >= 256 is a multiple of 4 whose number of 128-column tiles is even, B and C
+ * are 16-byte aligned and B is below 4 GiB; other calls are unaffected.  C is bit-identical
+ * in both modes. */
+enum spmm_tile_sharing { SPMM_SHARE_NONE = 0, SPMM_SHARE_WORKGROUP = 1 };
+int spmm_plan_set_tile_sharing(spmm_plan_t *plan, int mode);
+
 /* ---------------------------------------------------------------------------
  * Row panels of 32 rows (Section 4, Eq. 5).  With TM = 32 a brick column holds up to two
  * 16x4 bricks (rows 0..15 and rows 16..31 of the super-panel) and the B rows loaded for it

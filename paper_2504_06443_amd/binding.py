@@ -29,6 +29,7 @@ ROUTE_AUTO, ROUTE_MFMA, ROUTE_VALU, ROUTE_CLASS = 0, 1, 2, 3
 ORDER_PANEL, ORDER_HEAVY_FIRST = 0, 1
 SPLIT_EQ7_NEAREST, SPLIT_EQ7_FROM2, SPLIT_NEVER = -1, 0, 1
 PRECISION_FP32, PRECISION_BF16X3, PRECISION_BF16X6 = 0, 1, 2
+SHARE_NONE, SHARE_WORKGROUP = 0, 1
 PRECISIONS = {"fp32": PRECISION_FP32, "bf16x3": PRECISION_BF16X3, "bf16x6": PRECISION_BF16X6}
 CLASS_NAMES = ("Low", "Medium", "High")
 
@@ -37,7 +38,7 @@ EXPORTED = (
     "spmm_plan_sizes",
     "spmm_plan_export",
     "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_plan_set_precision",
-    "spmm_plan_set_panel_height", "spmm_plan_tm32_sizes", "spmm_plan_tm32_export",
+    "spmm_plan_set_tile_sharing", "spmm_plan_set_panel_height", "spmm_plan_tm32_sizes", "spmm_plan_tm32_export",
     "spmm_partition_counts",
     "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error",
 )
@@ -99,6 +100,7 @@ _lib.spmm_plan_set_route.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_split.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_order.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_precision.argtypes = [_vp, C.c_int]
+_lib.spmm_plan_set_tile_sharing.argtypes = [_vp, C.c_int]
 _lib.spmm_plan_set_panel_height.argtypes = [_vp, C.c_int, C.c_uint32, C.c_uint32, _vp]
 _lib.spmm_plan_tm32_sizes.argtypes = [_vp, C.POINTER(_Tm32Sizes)]
 _lib.spmm_plan_tm32_export.argtypes = [_vp] + [_vp] * 8
@@ -238,6 +240,10 @@ def spmm_plan_set_order(plan: Plan, order: int):
 
 def spmm_plan_set_precision(plan: Plan, precision: int):
     _check(_lib.spmm_plan_set_precision(plan._h, precision))
+
+
+def spmm_plan_set_tile_sharing(plan: Plan, mode: int):
+    _check(_lib.spmm_plan_set_tile_sharing(plan._h, mode))
 
 
 def spmm_plan_set_panel_height(plan: Plan, rows: int, merge_num: int = 6, merge_den: int = 5,

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspmm_brick.so")
-SOURCES = ("api.hip", "plan_kernels.hip", "exec_kernels.hip", "exec_bf16.hip",
+SOURCES = ("api.hip", "plan_kernels.hip", "exec_kernels.hip", "exec_wide.hip", "exec_bf16.hip",
            "tm32_kernels.hip")
 
 FLAGS = [

@@ -100,6 +100,7 @@ struct spmm_plan {
   int split = 0;
   int order = SPMM_ORDER_PANEL;
   int precision = SPMM_PRECISION_FP32;
+  int tile_sharing = SPMM_SHARE_NONE;
   // 32-row panel format (built on request; Section 4, Eq. 5)
   int panel_height = 16;
   struct Tm32 {
@@ -818,6 +819,9 @@ int launch_product(const spmm_plan_t* pl, const HostList* hl, const WorkItem* d_
     if (pl->precision != SPMM_PRECISION_FP32 && aligned && bf16_path_shape(N, pl->K))
       HIP_TRY(launch_spmm_bf16(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K,
                                pl->precision == SPMM_PRECISION_BF16X3 ? 2 : 3, pl->nnz, s));
+    else if (pl->tile_sharing == SPMM_SHARE_WORKGROUP && aligned && mfma_wide_waves(N, pl->K) > 0)
+      HIP_TRY(launch_spmm_mfma_wide(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N,
+                                    pl->K, s));
     else
       HIP_TRY(launch_spmm_mfma(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K,
                                s));
@@ -981,6 +985,14 @@ int spmm_plan_set_precision(spmm_plan_t* pl, int precision) {
   if (hipDeviceSynchronize() != hipSuccess) return fail(SPMM_EHIP, "hipDeviceSynchronize failed");
   pl->precision = precision;
   pl->drop_lists();   // the kernels differ in occupancy, which Eq. 7 uses
+  return SPMM_OK;
+}
+
+int spmm_plan_set_tile_sharing(spmm_plan_t* pl, int mode) {
+  if (!pl) return fail(SPMM_EINVAL, "plan is NULL");
+  if (mode != SPMM_SHARE_NONE && mode != SPMM_SHARE_WORKGROUP)
+    return fail(SPMM_EINVAL, "unknown tile-sharing mode");
+  pl->tile_sharing = mode;   // work lists do not depend on it
   return SPMM_OK;
 }
 

@@ -145,6 +145,13 @@ bool mfma_fast_shape(int64_t N, int64_t K);
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
                             int64_t K, hipStream_t s);
+// wide-N variant (exec_wide.hip): one workgroup per work item whose wavefronts take different
+// 128-column tiles and share the decoded bricks through LDS.  mfma_wide_waves: wavefronts per
+// workgroup it would use for (N, K), 0 when the shape is not served
+int mfma_wide_waves(int64_t N, int64_t K);
+hipError_t launch_spmm_mfma_wide(const BrickFormat& f, const WorkItem* items, int64_t n_items,
+                                 const float* B, float* C, float* partial, int64_t M, int64_t N,
+                                 int64_t K, hipStream_t s);
 // split-bf16 variant (exec_bf16.hip): planes = 2 or 3 bf16 terms per FP32 input
 bool bf16_path_shape(int64_t N, int64_t K);
 int bf16_resident_waves_per_cu(int64_t N, int planes);
