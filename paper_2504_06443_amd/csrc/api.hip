@@ -218,8 +218,10 @@ int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
       // AUTO is the measured policy for MI355X: the brick kernel wins wherever a B row is
       // worth loading once per panel instead of once per entry, which is everywhere except
       // Low-synergy panels (Table 1) at narrow N, where a brick feeds only one or two MFMAs
-      // and the CSR kernel packs 8 or 16 rows into a wavefront.
-      const bool low_to_csr = N <= 32;
+      // and the CSR kernel packs 8 or 16 rows into a wavefront.  A matrix with rows beyond the
+      // CSR kernel's side-by-side limit stays on the brick kernel altogether: such rows are the
+      // critical path of the CSR path, while the brick kernel splits their panels along K.
+      const bool low_to_csr = N <= 32 && pl->n_long_rows == 0;
       // an empty panel only needs its rows of C zeroed; either kernel does that, so it goes
       // where it does not cost a launch of its own
       if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_MFMA ||

@@ -528,18 +528,22 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu_rows(
   if (in_range) __builtin_nontemporal_store(acc, reinterpret_cast<float4_t*>(C + row * N + n));
 }
 
-// One workgroup per long row: its 4 * (64/LPR) lane groups take the row's entries in turn, four
-// at a time, and their partial sums are added in group order through LDS (deterministic).
-// `long_rows` lists every row of the matrix with more than kLongRow entries; rows whose panel
-// is not in the sorted list `panels` belong to the brick kernel and are skipped.
+// One workgroup of kLongWaves wavefronts per long row: its kLongWaves * (64/LPR) lane groups
+// take the row's entries in turn, four at a time, with the next four columns and values
+// fetched while the current B rows are in flight; the partial sums are added in group order
+// through LDS (deterministic).  `long_rows` lists every row of the matrix with more than
+// kLongRow entries; rows whose panel is not in the sorted list `panels` belong to the brick
+// kernel and are skipped.
+constexpr int kLongWaves = 16;
+
 template <int LPR>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu_long(
+__global__ __launch_bounds__(64 * kLongWaves) void k_spmm_valu_long(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
     const float* __restrict__ vals, const uint32_t* __restrict__ long_rows,
     const uint32_t* __restrict__ panels, int64_t n_panels, const float* __restrict__ B,
     float* __restrict__ C, int64_t N) {
   constexpr int R = 64 / LPR;
-  constexpr int G = R * kWavesPerBlock;    // lane groups of the workgroup
+  constexpr int G = R * kLongWaves;        // lane groups of the workgroup
   __shared__ float4_t part[G][LPR];
   const int64_t row = long_rows[blockIdx.x];
   const uint32_t panel = (uint32_t)(row / kPanel);
@@ -559,23 +563,32 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_valu_long(
   const int32_t s = rowptr[row], t = rowptr[row + 1];
   const float* __restrict__ Bn = B + (active ? n : 0);
   float4_t acc = {0.f, 0.f, 0.f, 0.f};
-  for (int32_t e = s + 4 * grp; e < t; e += 4 * G) {
-    int32_t c[4];
-    float a[4];
+  int32_t c[4];
+  float a[4];
+  auto fetch = [&](int32_t e, int32_t (&cc)[4], float (&aa)[4]) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {   // past the end: the last entry again, with a zero multiplier
+      const int32_t ex = min(e + x, t - 1);
+      cc[x] = colind[ex];
+      aa[x] = e + x < t ? vals[ex] : 0.f;
+    }
+  };
+  int32_t e = s + 4 * grp;
+  if (e < t) fetch(e, c, a);
+  for (; e < t; e += 4 * G) {
     float4_t b[4];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      const int32_t ex = min(e + x, t - 1);
-      c[x] = colind[ex];
-      a[x] = e + x < t ? vals[ex] : 0.f;
-    }
-#pragma unroll
     for (int x = 0; x < 4; ++x) b[x] = *reinterpret_cast<const float4_t*>(Bn + (int64_t)c[x] * N);
+    int32_t cn[4];
+    float an[4];
+    fetch(e + 4 * G, cn, an);
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
 #pragma unroll
       for (int w = 0; w < 4; ++w) acc[w] = fmaf(a[x], b[x][w], acc[w]);
     }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { c[x] = cn[x]; a[x] = an[x]; }
   }
   part[grp][gl] = acc;
   __syncthreads();
@@ -729,7 +742,7 @@ hipError_t launch_spmm_valu(const int32_t* rowptr, const int32_t* colind, const 
                        rowptr, colind, vals, panels, n_panels, B, C, M, N);                     \
     if (n_long_rows > 0)                                                                        \
       hipLaunchKernelGGL(k_spmm_valu_long<L>, dim3((unsigned)n_long_rows, gy),                  \
-                         dim3(64 * kWavesPerBlock), 0, s, rowptr, colind, vals, long_rows,      \
+                         dim3(64 * kLongWaves), 0, s, rowptr, colind, vals, long_rows,          \
                          panels, n_panels, B, C, N);                                            \
   } while (0)
     switch (lpr) {

@@ -405,7 +405,7 @@ def test_auto_routing_sends_low_synergy_panels_to_csr_only_at_narrow_widths(gpu)
     fewer than 8 stored elements per brick on average) when N <= 32.  The expected panel sets
     come from the oracle's format; the product is checked at both kinds of width."""
     top = W.clustered_blocks(1536, 6, 90, seed=50)                     # Medium panels
-    low = W.power_law(M=1500, target_nnz=None, cap=300, seed=51)        # Low panels, some empty
+    low = W.power_law(M=1500, target_nnz=None, cap=200, seed=51)        # Low panels, some empty
     rows = np.concatenate([np.repeat(np.arange(top.M), np.diff(top.rowptr)),
                            top.M + np.repeat(np.arange(low.M), np.diff(low.rowptr))])
     A = W.csr_from_coo(top.M + low.M, max(top.K, low.K), rows,
@@ -428,6 +428,19 @@ def test_auto_routing_sends_low_synergy_panels_to_csr_only_at_narrow_widths(gpu)
         B = W.dense_b(A.K, N, 3)
         Cref, S = oracle.spmm_f64(A.rowptr, A.colind, A.vals, B)
         check_c(run_product(gpu, plan, A, B, route=gpu.ROUTE_AUTO), Cref, S)
+    # one row beyond the CSR kernel's side-by-side limit (256 entries) keeps every panel on the
+    # brick kernel, which splits heavy panels along K instead of serialising on the long row
+    long_row = np.sort(np.random.default_rng(52).choice(A.K, size=300, replace=False))
+    rows2 = np.concatenate([rows, np.full(300, A.M)])
+    A2 = W.csr_from_coo(A.M + 1, A.K, rows2,
+                        np.concatenate([top.colind, low.colind, long_row.astype(np.int32)]),
+                        np.concatenate([top.vals, low.vals, np.ones(300, np.float32)]))
+    plan2 = make_plan(gpu, A2)
+    for N in (16, 32, 128):
+        assert gpu.spmm_plan_worklist(plan2, N)["n_valu_panels"] == 0, N
+    B = W.dense_b(A2.K, 32, 4)
+    Cref, S = oracle.spmm_f64(A2.rowptr, A2.colind, A2.vals, B)
+    check_c(run_product(gpu, plan2, A2, B, route=gpu.ROUTE_AUTO), Cref, S)
 
 
 def test_error_paths_on_device(gpu):
