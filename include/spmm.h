@@ -108,7 +108,8 @@ int spmm_plan_update_values(spmm_plan_t *plan, const float *vals, void *stream);
  * result is deterministic for a given plan, N and device.  The first call for a
  * new N builds and caches that N's work list (a host computation plus one small
  * upload, which synchronises the stream once); later calls allocate nothing.
- * A plan must not be used by two spmm_exec calls at the same time.
+ * A plan must not be used by two spmm_exec calls at the same time.  The device the plan
+ * was made on must be the current device (SPMM_EINVAL otherwise).
  */
 int spmm_exec(spmm_plan_t *plan, const float *B, int64_t N, float *C, void *stream);
 

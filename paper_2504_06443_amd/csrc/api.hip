@@ -517,11 +517,11 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   const int64_t P = (M + kPanel - 1) / kPanel;
   pl->M = M; pl->K = K; pl->nnz = nnz; pl->P = P;
 
-  // Device memory comes from three allocations (four on the search-based path): scratch
-  // (freed before returning), the plan's fixed-size arrays, and the brick arrays once their
+  // Device memory comes from three allocations (four on the search-based path): working
+  // arrays (`work`, freed before returning), the plan's fixed-size arrays, and the brick arrays once their
   // count is known.  Sub-arrays are 256-byte aligned.
   auto need = [](int64_t n, size_t elem) { return Arena::pad((size_t)std::max<int64_t>(n, 1) * elem); };
-  Arena scratch, wide, fixed, bricks;
+  Arena work, wide, fixed, bricks;
   uint32_t *d_err, *d_span, *d_maxnb, *scan_tmp, *nbricks_p, *panel_nnzptr, *ncols_p;
   enum { kPathSearch, kPathBitmap, kPathSort } path = kPathSearch;
   uint32_t sort_cap = 0;
@@ -568,20 +568,20 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
   HIP_TRY(hipDeviceGetAttribute(&pl->num_cus, hipDeviceAttributeMultiprocessorCount, pl->device));
   pl->num_cus = std::max(1, pl->num_cus);
 
-  scratch.cap = need(4, 4) + need(scan_elems, 4) + 2 * need(P, 4) + need(P + 1, 4) + need(K, 1) +
+  work.cap = need(4, 4) + need(scan_elems, 4) + 2 * need(P, 4) + need(P + 1, 4) + need(K, 1) +
                 need(P, 1) + need(kNumCounters, 8) + need(1, 8);
-  HIP_TRY(hipMalloc((void**)&scratch.base, scratch.cap));
-  d_err = scratch.take<uint32_t>(4);   // error bits, widest span, most entries, most columns
+  HIP_TRY(hipMalloc((void**)&work.base, work.cap));
+  d_err = work.take<uint32_t>(4);   // error bits, widest span, most entries, most columns
   d_span = d_err + 1;
   d_maxnb = d_err + 3;
-  scan_tmp = scratch.take<uint32_t>(scan_elems);
-  nbricks_p = scratch.take<uint32_t>(P);
-  ncols_p = scratch.take<uint32_t>(P);
-  panel_nnzptr = scratch.take<uint32_t>(P + 1);
-  col_seen = scratch.take<uint8_t>(K);
-  panel_class = scratch.take<uint8_t>(P);
-  counters = scratch.take<unsigned long long>(kNumCounters);
-  d_active = scratch.take<unsigned long long>(1);
+  scan_tmp = work.take<uint32_t>(scan_elems);
+  nbricks_p = work.take<uint32_t>(P);
+  ncols_p = work.take<uint32_t>(P);
+  panel_nnzptr = work.take<uint32_t>(P + 1);
+  col_seen = work.take<uint8_t>(K);
+  panel_class = work.take<uint8_t>(P);
+  counters = work.take<unsigned long long>(kNumCounters);
+  d_active = work.take<unsigned long long>(1);
 
   fixed.cap = need(P + 1, 4) + need(M + 1, 4) + 3 * need(nnz, 4) +
               need(nnz / long_row_threshold() + 1, 4);
@@ -755,7 +755,7 @@ int spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const in
 
 done:
   if (status != SPMM_OK) (void)hipStreamSynchronize(s);
-  if (scratch.base) (void)hipFree(scratch.base);
+  if (work.base) (void)hipFree(work.base);
   if (wide.base) (void)hipFree(wide.base);
   if (status != SPMM_OK) {
     delete pl;
@@ -789,6 +789,10 @@ int check_exec_args(const spmm_plan_t* pl, const float* B, int64_t N, const floa
   if (N == 0 || pl->M == 0) return 1;   // nothing to do
   if (!C) return fail(SPMM_EINVAL, "C is NULL");
   if (!B && pl->K > 0) return fail(SPMM_EINVAL, "B is NULL");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != pl->device)
+    return fail(SPMM_EINVAL, "the plan was made on device %d, the current device is %d",
+                pl->device, dev);
   return SPMM_OK;
 }
 
