@@ -830,7 +830,7 @@ int launch_product(const spmm_plan_t* pl, const HostList* hl, const WorkItem* d_
                                     pl->K, s));
     else
       HIP_TRY(launch_spmm_mfma(f, d_items, hl->info.n_mfma_items, B, C, d_partial, pl->M, N, pl->K,
-                               s));
+                               pl->nnz, s));
   }
   HIP_TRY(launch_spmm_valu(pl->rowptr, pl->colind, pl->csr_vals, d_valu_panels,
                            hl->info.n_valu_panels, pl->long_rows, pl->n_long_rows, B, C, pl->M, N,

@@ -30,6 +30,8 @@
 // multiple of four.  Used for the panels that the routing sends to the CSR path.
 #include "exec_common.h"
 
+#include <type_traits>
+
 namespace spmm {
 
 int long_row_threshold() { return 256; }
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma(
 // the traffic from memory.
 constexpr int kFastChunk = 8;
 
-template <int T>
+template <int T, bool FULL>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     const uint32_t* __restrict__ brick_cols, const uint64_t* __restrict__ brick_mask,
     const uint32_t* __restrict__ brick_valptr, const float* __restrict__ vals,
@@ -275,14 +277,14 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     };
     // lane 4*i + c: byte offset of B row brick_cols[4*(base+i) + c]; pad columns
     // (0xFFFFFFFF) clamp to the last row, which is harmless since A is 0 there
-    auto load_rowoff = [&](uint32_t base) {
+    auto load_col = [&](uint32_t base) {
       // steps past the work item's last brick re-read that brick's rows (cache hits) instead
       // of pulling the next panel's B rows through the memory system for nothing
       const uint32_t slot = (uint32_t)lane & (CH * kBrickK - 1);
       const uint32_t idx = min(base * kBrickK + slot, (b_end - 1) * kBrickK + (slot & (kBrickK - 1)));
-      const uint32_t c = brick_cols[idx];
-      return min(c, k_last) * row_bytes;
+      return brick_cols[idx];
     };
+    auto row_offset = [&](uint32_t col) { return min(col, k_last) * row_bytes; };
 
     uint64_t st_mask[R];
     float st_a[R];
@@ -300,11 +302,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
       st_mask[s] = mask;
       const uint32_t cnt = __builtin_amdgcn_mbcnt_hi(
           (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-      st_a[s] = vals[(int64_t)off + cnt];
+      // scalar base + 32-bit byte offset (the launcher checks that the values fit 4 GiB)
+      st_a[s] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(vals) +
+                                                (off * 4u + cnt * 4u));
+      const char* brow = Bbytes + (ro + lane_off[0]);
 #pragma unroll
       for (int q = 0; q < NV; ++q) {
         float tmp[V];
-        load_vec<V>(reinterpret_cast<const float*>(Bbytes + (ro + lane_off[q])), tmp);
+        // whole tiles: the q-th vector lies a constant distance behind the first
+        if constexpr (FULL) load_vec<V>(reinterpret_cast<const float*>(brow + q * 16 * V * 4), tmp);
+        else load_vec<V>(reinterpret_cast<const float*>(Bbytes + (ro + lane_off[q])), tmp);
 #pragma unroll
         for (int w = 0; w < V; ++w) st_b[s][q * V + w] = tmp[w];
       }
@@ -320,7 +327,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     };
 
     Meta cur = load_meta(b_begin);
-    uint32_t ro_cur = load_rowoff(b_begin);
+    uint32_t ro_cur = row_offset(load_col(b_begin));
     const uint32_t off_last = brick_valptr[b_end - 1];
     // keep the first fetch from being merged with the in-loop fetch into one
     // load at the top of the loop (which would expose its latency every chunk)
@@ -335,35 +342,60 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     // steps that hold no brick.
     const uint32_t total = nbricks + R;
     uint32_t ro_next = __builtin_amdgcn_ds_bpermute(perm_base, ro_cur);
-    auto step = [&](int i, uint32_t g, const Meta& m, uint32_t ro_this, uint32_t ro_following) {
-      if (g >= (uint32_t)R && g - R < nbricks) compute(i % R);
+    // `steady`: the chunk lies entirely inside the work item and behind its first R steps, so
+    // every step has a brick to compute and a brick to fetch and needs none of the checks
+    // col_following: the next chunk's columns as loaded at the start of this chunk; they are
+    // turned into row offsets in the chunk's last step, so that nothing waits for that load
+    // while the ring's loads are younger than it
+    uint32_t ro_following = 0;
+    auto step = [&](auto steady, int i, uint32_t g, const Meta& m, uint32_t ro_this,
+                    uint32_t col_following) {
+      constexpr bool kSteady = decltype(steady)::value;
+      if (kSteady || (g >= (uint32_t)R && g - R < nbricks)) compute(i % R);
       // this lane's row offset was fetched across lanes one step ago (its LDS-port latency
       // hides behind the MFMAs above); fetch the next brick's now
       const uint32_t ro = ro_next;
-      ro_next = (i + 1 < CH) ? __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_this)
-                             : __builtin_amdgcn_ds_bpermute(perm_base, ro_following);
-      const bool live = g < nbricks;   // uniform: scalar selects
+      if (i + 1 < CH) {
+        ro_next = __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_this);
+      } else {
+        ro_following = row_offset(col_following);
+        ro_next = __builtin_amdgcn_ds_bpermute(perm_base, ro_following);
+      }
+      const bool live = kSteady || g < nbricks;   // uniform: scalar selects
       issue(live ? m.mask[i] : 0ull, live ? m.off[i] : off_last, ro, i % R);
+      // without the branches of the checked variant the steps of a chunk are one basic block;
+      // keep the scheduler from sinking a step's loads down to their use R steps later
+      if constexpr (kSteady) __builtin_amdgcn_sched_barrier(0);
     };
-    // Whole chunks run in a loop whose only exit is at its top; the last, partial chunk is
-    // straight-line code after it.  With an exit in the middle of the loop body the compiler
+    // Whole chunks run in loops whose only exit is at their top; the last, partial chunk is
+    // straight-line code after them.  With an exit in the middle of a loop body the compiler
     // must assume, at the loop head, that the steps after that exit issued no loads (it
     // cannot see that the loop ends on that path), and it then waits for all but the newest
     // load at the start of every chunk, which empties the ring every CH bricks.
+    // Three phases: the first chunk (its first R steps have nothing to compute), the chunks
+    // that lie entirely inside the work item (no checks), and the one or two chunks around its
+    // end.  Every chunk issues the same loads in the same order, so the count of loads in
+    // flight is the same on every path into a loop head.
     uint32_t c = 0;
-    for (; c + CH <= total; c += CH) {
+    auto chunk = [&](auto steady) {
       const Meta nxt = load_meta(b_begin + c + CH);
-      const uint32_t ro_nxt = load_rowoff(b_begin + c + CH);
+      const uint32_t col_nxt = load_col(b_begin + c + CH);
 #pragma unroll
-      for (int i = 0; i < CH; ++i) step(i, c + i, cur, ro_cur, ro_nxt);
+      for (int i = 0; i < CH; ++i) step(steady, i, c + i, cur, ro_cur, col_nxt);
       cur = nxt;
-      ro_cur = ro_nxt;
+      ro_cur = ro_following;
+    };
+    if (c + CH <= total) {
+      chunk(std::false_type{});
+      c += CH;
     }
+    for (; c + CH <= nbricks; c += CH) chunk(std::true_type{});
+    for (; c + CH <= total; c += CH) chunk(std::false_type{});
     if (c < total) {
 #pragma unroll
       for (int i = 0; i < CH; ++i) {
         if (i % R == 0 && i > 0 && c + i >= total) break;
-        step(i, c + i, cur, ro_cur, ro_cur);
+        step(std::false_type{}, i, c + i, cur, ro_cur, 0u);   // its last step fetches nothing real
       }
     }
   }
@@ -649,7 +681,7 @@ int occupancy_t() {
 template <int T>
 int occupancy_fast_t() {
   int nb = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_spmm_mfma_fast<T>, 64 * kWavesPerBlock,
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_spmm_mfma_fast<T, false>, 64 * kWavesPerBlock,
                                                    0) != hipSuccess || nb < 1)
     nb = 1;
   return nb * kWavesPerBlock;
@@ -689,25 +721,28 @@ int mfma_resident_waves_per_cu(int64_t N, int64_t K) {
 
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
-                            int64_t K, hipStream_t s) {
+                            int64_t K, int64_t nnz, hipStream_t s) {
   if (n_items == 0 || N == 0) return hipSuccess;
   const int tile = mfma_tile_for(N);
   const int V = tile >= 64 ? 4 : tile / 16;
   const bool al = (N % V == 0) && ptr_aligned16(B) && ptr_aligned16(C) &&
                   (partial == nullptr || ptr_aligned16(partial));
-  if (al && mfma_fast_shape(N, K)) {
+  // the fast kernel addresses the packed values (and their 64 spare floats) by 32-bit byte offsets
+  if (al && mfma_fast_shape(N, K) && nnz + 64 < (int64_t(1) << 30)) {
     unsigned gx = (unsigned)((n_items + kWavesPerBlock - 1) / kWavesPerBlock);
     gx = (gx + kXcds - 1) / kXcds * kXcds;  // whole rounds over the XCDs
     const dim3 grid(gx, (unsigned)((N + tile - 1) / tile)), block(64 * kWavesPerBlock);
     const uint32_t k_last = (uint32_t)(K - 1);
-#define SPMM_LAUNCH_FAST(TT)                                                              \
-  hipLaunchKernelGGL((k_spmm_mfma_fast<TT>), grid, block, 0, s, f.brick_cols, f.brick_mask, \
+#define SPMM_LAUNCH_FAST(TT, FF)                                                                \
+  hipLaunchKernelGGL((k_spmm_mfma_fast<TT, FF>), grid, block, 0, s, f.brick_cols, f.brick_mask, \
                      f.brick_valptr, f.vals, items, n_items, B, C, partial, M, N, k_last)
     switch (tile) {
-      case 16: SPMM_LAUNCH_FAST(1); break;
-      case 32: SPMM_LAUNCH_FAST(2); break;
-      case 64: SPMM_LAUNCH_FAST(4); break;
-      default: SPMM_LAUNCH_FAST(8); break;
+      case 16: SPMM_LAUNCH_FAST(1, false); break;
+      case 32: SPMM_LAUNCH_FAST(2, false); break;
+      case 64: SPMM_LAUNCH_FAST(4, false); break;
+      default:   // whole 128-column tiles: the second vector of a B row at a constant offset
+        if (N % 128 == 0) SPMM_LAUNCH_FAST(8, true); else SPMM_LAUNCH_FAST(8, false);
+        break;
     }
 #undef SPMM_LAUNCH_FAST
     return hipGetLastError();

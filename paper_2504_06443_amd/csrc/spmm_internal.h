@@ -144,7 +144,7 @@ int mfma_resident_waves_per_cu(int64_t N, int64_t K);
 bool mfma_fast_shape(int64_t N, int64_t K);
 hipError_t launch_spmm_mfma(const BrickFormat& f, const WorkItem* items, int64_t n_items,
                             const float* B, float* C, float* partial, int64_t M, int64_t N,
-                            int64_t K, hipStream_t s);
+                            int64_t K, int64_t nnz, hipStream_t s);
 // wide-N variant (exec_wide.hip): one workgroup per work item whose wavefronts take different
 // 128-column tiles and share the decoded bricks through LDS.  mfma_wide_waves: wavefronts per
 // workgroup it would use for (N, K), 0 when the shape is not served
