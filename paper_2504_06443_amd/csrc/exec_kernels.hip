@@ -237,13 +237,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
 
   const int lane = threadIdx.x & 63;
   const uint32_t vblock = xcd_contiguous_block();   // contiguous range of work items per XCD
-  const int64_t item_id = (int64_t)vblock * kWavesPerBlock + (threadIdx.x >> 6);
+  // the wavefront's index as a scalar, so that its work item comes through the scalar cache
+  // (one round trip less through the vector-memory path before the first brick)
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t item_id = (int64_t)vblock * kWavesPerBlock + wave;
   if (item_id >= n_items) return;  // whole wavefront leaves together
   const WorkItem it = items[item_id];
-  const uint32_t panel = __builtin_amdgcn_readfirstlane(it.panel);
-  const uint32_t b_begin = __builtin_amdgcn_readfirstlane(it.brick_begin);
-  const uint32_t b_end = __builtin_amdgcn_readfirstlane(it.brick_end);
-  const uint32_t slot = __builtin_amdgcn_readfirstlane(it.slot);
+  const uint32_t panel = it.panel;
+  const uint32_t b_begin = it.brick_begin;
+  const uint32_t b_end = it.brick_end;
+  const uint32_t slot = it.slot;
 
   const int j = lane & 15;
   const int kq = lane >> 4;

@@ -37,11 +37,11 @@ __global__ __launch_bounds__(64 * W) void k_spmm_mfma_wide(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t item_id = xcd_contiguous_block();   // one work item per workgroup
   if (item_id >= n_items) return;                   // the whole workgroup leaves together
-  const WorkItem it = items[item_id];
-  const uint32_t panel = __builtin_amdgcn_readfirstlane(it.panel);
-  const uint32_t b_begin = __builtin_amdgcn_readfirstlane(it.brick_begin);
-  const uint32_t b_end = __builtin_amdgcn_readfirstlane(it.brick_end);
-  const uint32_t slot = __builtin_amdgcn_readfirstlane(it.slot);
+  const WorkItem it = items[item_id];   // uniform index: through the scalar cache
+  const uint32_t panel = it.panel;
+  const uint32_t b_begin = it.brick_begin;
+  const uint32_t b_end = it.brick_end;
+  const uint32_t slot = it.slot;
 
   const int j = lane & 15;
   const int kq = lane >> 4;
