@@ -273,6 +273,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true",
                     help="time only --workload (the default run adds two more workloads under `extra`)")
     ap.add_argument("--sweep", action="store_true", help="print the synergy-sweep grid instead")
+    ap.add_argument("--calibrate-gather", action="store_true",
+                    help="measure the random-row gather bandwidth of this GPU (the memory ceiling "
+                         "for inputs whose B rows cannot be reused) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (1 GiB, 10 times): the "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -303,6 +306,27 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": n * 4, "calibrate_copy_bytes_written": n * 4,
                           "launches": 10}), flush=True)
+        return
+    if args.calibrate_gather:
+        # what the memory system delivers for the brick kernel's way of reading B (random rows of
+        # 512 bytes), from buffers that fit one L2, the L2s together, the Infinity Cache, and only HBM
+        sink = torch.zeros(256, dtype=torch.float32, device=dev)
+        buf = torch.zeros((2 << 30) // 4, dtype=torch.float32, device=dev)
+        st = torch.cuda.current_stream()
+        n_waves, loads = 256 * 16, 2048
+        for mb in (2, 16, 128, 2048):
+            n_rows = (mb << 20) // 512
+            for _ in range(2):
+                spmm.spmm_calibrate_gather(buf, n_rows, loads, n_waves, sink, st)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(5):
+                spmm.spmm_calibrate_gather(buf, n_rows, loads, n_waves, sink, st)
+            e1.record(st)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            print(json.dumps({"calibrate_gather_buffer_MB": mb, "ms": ms,
+                              "TB_per_s": n_waves * loads * 1024 / (ms * 1e-3) / 1e12}), flush=True)
         return
     if args.sweep:
         sweep(spmm, args.steps, args.warmup)

@@ -318,6 +318,18 @@ int spmm_plan_worklist(spmm_plan_t *plan, int64_t N, spmm_worklist_info_t *info 
                        spmm_work_item_t *items /* host [n_mfma_items] or NULL */,
                        uint32_t *valu_panels /* host [n_valu_panels] or NULL */);
 
+/* Measurement aid (used by bench.py to calibrate the memory roofline of the brick kernel):
+ * enqueues one kernel in which each of n_waves wavefronts reads loads_per_wave x 1 KiB from
+ * `buf` the way the brick kernel reads B at N = 128 -- four rows of 512 bytes picked at
+ * random per pair of load instructions, 16 lanes x 16 contiguous bytes per half row, 8 loads
+ * in flight.  The caller times it; bytes moved = n_waves * loads_per_wave * 1024.
+ *   buf     dev, n_rows * 512 bytes, finite values; n_rows a power of two
+ *   loads_per_wave  multiple of 8;  n_waves  multiple of 4
+ *   sink    dev float[256], never written for finite inputs (keeps the loads alive)
+ * SPMM_EINVAL for sizes outside these rules. */
+int spmm_calibrate_gather(const float *buf, int64_t n_rows, int64_t loads_per_wave,
+                          int64_t n_waves, float *sink, void *stream);
+
 void spmm_plan_destroy(spmm_plan_t *plan); /* NULL is allowed */
 
 const char *spmm_last_error(void); /* thread-local, valid until the next failing call */

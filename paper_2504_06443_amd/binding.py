@@ -40,7 +40,7 @@ EXPORTED = (
     "spmm_plan_set_route", "spmm_plan_set_split", "spmm_plan_set_order", "spmm_plan_set_precision",
     "spmm_plan_set_tile_sharing", "spmm_plan_set_panel_height", "spmm_plan_tm32_sizes", "spmm_plan_tm32_export",
     "spmm_partition_counts",
-    "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error",
+    "spmm_plan_worklist", "spmm_plan_destroy", "spmm_last_error", "spmm_calibrate_gather",
 )
 
 
@@ -108,6 +108,7 @@ _lib.spmm_partition_counts.argtypes = [C.c_int64, _vp, C.c_int64, C.c_int32, C.c
                                        _vp, C.POINTER(C.c_int64)]
 _lib.spmm_plan_worklist.argtypes = [_vp, C.c_int64, C.POINTER(_WorklistInfo), _vp, _vp]
 _lib.spmm_plan_destroy.argtypes = [_vp]
+_lib.spmm_calibrate_gather.argtypes = [_vp, C.c_int64, C.c_int64, C.c_int64, _vp, _vp]
 _lib.spmm_plan_destroy.restype = None
 
 
@@ -240,6 +241,16 @@ def spmm_plan_set_order(plan: Plan, order: int):
 
 def spmm_plan_set_precision(plan: Plan, precision: int):
     _check(_lib.spmm_plan_set_precision(plan._h, precision))
+
+
+def spmm_calibrate_gather(buf, n_rows: int, loads_per_wave: int, n_waves: int, sink, stream=None):
+    """Enqueue the random-row gather kernel (measurement aid); the caller times it."""
+    if buf.numel() * buf.element_size() < n_rows * 512 or sink.numel() < 256:
+        raise ValueError("buffer too small")
+    status = _lib.spmm_calibrate_gather(_dev(buf, torch.float32), n_rows, loads_per_wave, n_waves,
+                                        _dev(sink, torch.float32), _stream_ptr(stream))
+    if status != SPMM_OK:
+        raise SpmmError(status, "spmm_calibrate_gather: bad sizes")
 
 
 def spmm_plan_set_tile_sharing(plan: Plan, mode: int):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspmm_brick.so")
 SOURCES = ("api.hip", "plan_kernels.hip", "exec_kernels.hip", "exec_wide.hip", "exec_bf16.hip",
-           "tm32_kernels.hip")
+           "tm32_kernels.hip", "calibrate.hip")
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
