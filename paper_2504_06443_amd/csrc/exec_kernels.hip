@@ -319,15 +319,20 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
         for (int w = 0; w < V; ++w) st_b[s][q * V + w] = tmp[w];
       }
     };
-    auto compute = [&](int s) {
+    // the A operand of the brick in stage s: zero fill, then the transposition
+    auto operand = [&](int s) {
       float in_bit_order;
       asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(in_bit_order) : "v"(st_a[s]), "s"(st_mask[s]));
-      const float a = __builtin_bit_cast(
+      return __builtin_bit_cast(
           float, __builtin_amdgcn_ds_bpermute(perm_transpose, __builtin_bit_cast(int, in_bit_order)));
+    };
+    auto multiply = [&](float a, int s) {
 #pragma unroll
       for (int u = 0; u < T; ++u)
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, st_b[s][u], acc[u], 0, 0, 0);
     };
+    auto compute = [&](int s) { multiply(operand(s), s); };
+    float a_ahead = 0.f;   // steady chunks: the next step's A operand, made one step early
 
     Meta cur = load_meta(b_begin);
     uint32_t ro_cur = row_offset(load_col(b_begin));
@@ -354,7 +359,14 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
     auto step = [&](auto steady, int i, uint32_t g, const Meta& m, uint32_t ro_this,
                     uint32_t col_following) {
       constexpr bool kSteady = decltype(steady)::value;
-      if (kSteady || (g >= (uint32_t)R && g - R < nbricks)) compute(i % R);
+      if constexpr (kSteady) {
+        // the cross-lane move of the next brick's operand runs under this brick's MFMAs
+        const float a = a_ahead;
+        a_ahead = operand((i + 1) % R);
+        multiply(a, i % R);
+      } else {
+        if (g >= (uint32_t)R && g - R < nbricks) compute(i % R);
+      }
       // this lane's row offset was fetched across lanes one step ago (its LDS-port latency
       // hides behind the MFMAs above); fetch the next brick's now
       const uint32_t ro = ro_next;
@@ -392,6 +404,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_mfma_fast(
       chunk(std::false_type{});
       c += CH;
     }
+    if (c + CH <= nbricks) a_ahead = operand(0);   // c is a multiple of CH, so stage 0 is next
     for (; c + CH <= nbricks; c += CH) chunk(std::true_type{});
     for (; c + CH <= total; c += CH) chunk(std::false_type{});
     if (c < total) {
