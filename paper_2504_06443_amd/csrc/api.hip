@@ -802,6 +802,7 @@ bool uses_tm32(const spmm_plan_t* pl, const float* B, int64_t N, const float* C)
   if (pl->panel_height != 32 || !pl->tm32.arena) return false;
   if (pl->route != SPMM_ROUTE_AUTO && pl->route != SPMM_ROUTE_MFMA) return false;
   if (pl->precision != SPMM_PRECISION_FP32) return false;
+  if (pl->nnz + 64 >= (int64_t(1) << 30)) return false;   // the kernel's 32-bit value offsets
   return mfma_fast_shape(N, pl->K) && ptr_is_aligned16(B) && ptr_is_aligned16(C);
 }
 

@@ -18,6 +18,8 @@
 // of its top and bottom brick (zero pattern where a half has no brick).
 #include "exec_common.h"
 
+#include <type_traits>
+
 namespace spmm {
 
 namespace {
@@ -267,10 +269,11 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
 
   const int lane = threadIdx.x & 63;
   const uint32_t vblock = xcd_contiguous_block();
-  const int64_t q = (int64_t)vblock * kWavesPerBlock + (threadIdx.x >> 6);
+  // the wavefront's index as a scalar: its range comes through the scalar cache
+  const int64_t q = (int64_t)vblock * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   if (q >= Q) return;  // whole wavefront leaves together
-  const uint32_t k_begin = __builtin_amdgcn_readfirstlane(sp_ptr[q]);
-  const uint32_t k_end = __builtin_amdgcn_readfirstlane(sp_ptr[q + 1]);
+  const uint32_t k_begin = sp_ptr[q];
+  const uint32_t k_end = sp_ptr[q + 1];
 
   const int j = lane & 15;
   const int kq = lane >> 4;
@@ -306,11 +309,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
     };
     // lane 4*i + c: byte offset of B row bc_cols[4*(base+i) + c]; steps past the last brick
     // column re-read that column's rows (cache hits)
-    auto load_rowoff = [&](uint32_t base) {
+    auto load_col = [&](uint32_t base) {
       const uint32_t slot = (uint32_t)lane & (CH * kBrickK - 1);
       const uint32_t idx = min(base * kBrickK + slot, (k_end - 1) * kBrickK + (slot & (kBrickK - 1)));
-      return min(bc_cols[idx], k_last) * row_bytes;
+      return bc_cols[idx];
     };
+    auto row_offset = [&](uint32_t col) { return min(col, k_last) * row_bytes; };
 
     uint64_t st_mt[R], st_mb[R];
     float st_at[R], st_ab[R];
@@ -322,8 +326,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mt, 0u));
       const uint32_t cb = __builtin_amdgcn_mbcnt_hi((uint32_t)(mb >> 32),
                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mb, 0u));
-      st_at[s] = (vals + ot)[ct];
-      st_ab[s] = (vals + ob)[cb];
+      // scalar base + 32-bit byte offset (the launcher's caller checks that the values fit)
+      const char* vbytes = reinterpret_cast<const char*>(vals);
+      st_at[s] = *reinterpret_cast<const float*>(vbytes + (ot * 4u + ct * 4u));
+      st_ab[s] = *reinterpret_cast<const float*>(vbytes + (ob * 4u + cb * 4u));
 #pragma unroll
       for (int qv = 0; qv < NV; ++qv) {
         float tmp[V];
@@ -347,36 +353,54 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
     };
 
     Chunk cur = load_meta(k_begin);
-    uint32_t ro_cur = load_rowoff(k_begin);
+    uint32_t ro_cur = row_offset(load_col(k_begin));
     asm volatile("" : "+v"(ro_cur));
 #pragma unroll
     for (int i = 0; i < CH; ++i)
       asm volatile("" : "+s"(cur.mt[i]), "+s"(cur.mb[i]), "+s"(cur.ot[i]), "+s"(cur.ob[i]));
 
+    // Step g computes brick column g-R from stage g%R and refills that stage with brick column
+    // g.  Chunks that lie inside the super-panel and behind its first R steps ("steady") need
+    // none of the per-step checks; scheduling barriers keep their steps in order (see the
+    // 16-row kernel).  The next chunk's columns become row offsets in the chunk's last step.
     const uint32_t total = ncols + R;
     uint32_t ro_next = __builtin_amdgcn_ds_bpermute(perm_base, ro_cur);
-    auto step = [&](int i, uint32_t g, const Chunk& m, uint32_t ro_this, uint32_t ro_following) {
-      if (g >= (uint32_t)R && g - R < ncols) compute(i % R);
+    uint32_t ro_following = 0;
+    auto step = [&](auto steady, int i, uint32_t g, const Chunk& m, uint32_t ro_this,
+                    uint32_t col_following) {
+      constexpr bool kSteady = decltype(steady)::value;
+      if (kSteady || (g >= (uint32_t)R && g - R < ncols)) compute(i % R);
       const uint32_t ro = ro_next;
-      ro_next = (i + 1 < CH) ? __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_this)
-                             : __builtin_amdgcn_ds_bpermute(perm_base, ro_following);
-      const bool live = g < ncols;   // uniform: scalar selects
+      if (i + 1 < CH) {
+        ro_next = __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_this);
+      } else {
+        ro_following = row_offset(col_following);
+        ro_next = __builtin_amdgcn_ds_bpermute(perm_base, ro_following);
+      }
+      const bool live = kSteady || g < ncols;   // uniform: scalar selects
       issue(live ? m.mt[i] : 0ull, live ? m.mb[i] : 0ull, m.ot[i], m.ob[i], ro, i % R);
+      if constexpr (kSteady) __builtin_amdgcn_sched_barrier(0);
     };
     uint32_t c = 0;
-    for (; c + CH <= total; c += CH) {
+    auto chunk = [&](auto steady) {
       const Chunk nxt = load_meta(k_begin + c + CH);
-      const uint32_t ro_nxt = load_rowoff(k_begin + c + CH);
+      const uint32_t col_nxt = load_col(k_begin + c + CH);
 #pragma unroll
-      for (int i = 0; i < CH; ++i) step(i, c + i, cur, ro_cur, ro_nxt);
+      for (int i = 0; i < CH; ++i) step(steady, i, c + i, cur, ro_cur, col_nxt);
       cur = nxt;
-      ro_cur = ro_nxt;
+      ro_cur = ro_following;
+    };
+    if (c + CH <= total) {
+      chunk(std::false_type{});
+      c += CH;
     }
+    for (; c + CH <= ncols; c += CH) chunk(std::true_type{});
+    for (; c + CH <= total; c += CH) chunk(std::false_type{});
     if (c < total) {
 #pragma unroll
       for (int i = 0; i < CH; ++i) {
         if (i % R == 0 && i > 0 && c + i >= total) break;
-        step(i, c + i, cur, ro_cur, ro_cur);
+        step(std::false_type{}, i, c + i, cur, ro_cur, 0u);
       }
     }
   }

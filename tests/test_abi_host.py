@@ -98,6 +98,16 @@ def test_null_plan_is_an_error_not_a_crash(binding):
     assert binding._lib.spmm_plan_sizes(None, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_plan_update_values(None, None, None) == binding.SPMM_EINVAL
     assert binding._lib.spmm_plan_set_order(None, 0) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_plan_set_precision(None, 0) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_plan_set_tile_sharing(None, 0) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_plan_set_panel_height(None, 32, 6, 5, None) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_plan_tm32_sizes(None, None) == binding.SPMM_EINVAL
+    # the measurement aid checks its sizes before it touches the GPU
+    assert binding._lib.spmm_calibrate_gather(None, 1024, 8, 4, None, None) == binding.SPMM_EINVAL
+    fake = ctypes.c_void_p(4096)   # never dereferenced: the size rules fail first
+    assert binding._lib.spmm_calibrate_gather(fake, 1000, 8, 4, fake, None) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_calibrate_gather(fake, 1024, 7, 4, fake, None) == binding.SPMM_EINVAL
+    assert binding._lib.spmm_calibrate_gather(fake, 1024, 8, 3, fake, None) == binding.SPMM_EINVAL
     binding._lib.spmm_plan_destroy(None)
     out = ctypes.c_void_p()
     assert binding._lib.spmm_plan(-1, 1, 0, None, None, None, None, ctypes.byref(out)) == binding.SPMM_EINVAL

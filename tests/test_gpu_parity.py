@@ -443,6 +443,20 @@ def test_auto_routing_sends_low_synergy_panels_to_csr_only_at_narrow_widths(gpu)
     check_c(run_product(gpu, plan2, A2, B, route=gpu.ROUTE_AUTO), Cref, S)
 
 
+def test_gather_calibration_runs(gpu):
+    """The measurement aid reads only inside the buffer it is given and leaves the sink alone."""
+    import torch
+    buf = torch.ones(1 << 20, dtype=torch.float32, device="cuda")      # 4 MiB = 8192 rows
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    gpu.spmm_calibrate_gather(buf, 8192, 64, 1024, sink)
+    torch.cuda.synchronize()
+    assert not sink.any()
+    with pytest.raises(ValueError):
+        gpu.spmm_calibrate_gather(buf, 16384, 64, 1024, sink)             # buffer too small
+    with pytest.raises(gpu.SpmmError):
+        gpu.spmm_calibrate_gather(buf, 8192, 60, 1024, sink)              # loads not a multiple of 8
+
+
 def test_error_paths_on_device(gpu):
     import ctypes
     import torch
