@@ -36,10 +36,8 @@ enum spmm_status {
 enum spmm_route {
   SPMM_ROUTE_AUTO = 0,  /* the measured policy for MI355X: the MFMA brick kernel for every
                            panel (it loads each B row of a panel once, CSR loads it once per
-                           entry), except that panels of Low synergy (Table 1) go to the CSR
-                           kernel when N <= 32, where a brick feeds only one or two MFMAs,
-                           provided no row of the matrix has more than 256 entries (such rows
-                           are the CSR kernel's critical path)                               */
+                           entry; on the fill x width map of config 5 the CSR kernel is
+                           nowhere ahead by more than a few percent)                         */
   SPMM_ROUTE_MFMA = 1,  /* every panel through the MFMA brick kernel (an empty panel is a work
                            item without bricks that stores zeros)                            */
   SPMM_ROUTE_VALU = 2,  /* every panel through the vector-ALU CSR kernel                      */

@@ -215,21 +215,16 @@ int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
     for (int64_t p = 0; p < pl->P; ++p) {
       const uint8_t cls = pl->h_panel_class[p];
       bool to_mfma;
-      // AUTO is the measured policy for MI355X: the brick kernel wins wherever a B row is
-      // worth loading once per panel instead of once per entry, which is everywhere except
-      // Low-synergy panels (Table 1) at narrow N, where a brick feeds only one or two MFMAs
-      // and the CSR kernel packs 8 or 16 rows into a wavefront.  A matrix with rows beyond the
-      // CSR kernel's side-by-side limit stays on the brick kernel altogether: such rows are the
-      // critical path of the CSR path, while the brick kernel splits their panels along K.
-      const bool low_to_csr = N <= 32 && pl->n_long_rows == 0;
-      // an empty panel only needs its rows of C zeroed; either kernel does that, so it goes
-      // where it does not cost a launch of its own
-      if (cls == 255) to_mfma = pl->route == SPMM_ROUTE_MFMA ||
-                                (pl->route == SPMM_ROUTE_AUTO && !low_to_csr);
-      else if (pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
+      // AUTO is the measured policy for MI355X: the brick kernel loads each B row of a panel
+      // once where CSR loads it once per entry, and on the config-5 map (five fills x six
+      // widths) the CSR kernel is nowhere faster by more than a few percent (a tie at fill
+      // 0.05, N = 16), so every panel goes to the brick kernel.  SPMM_ROUTE_CLASS is the
+      // paper's per-class rule.
+      // An empty panel (class 255) only needs its rows of C zeroed; either kernel does that, so
+      // under CLASS it goes to the CSR kernel, whose launch the Low panels cause anyway.
+      if (pl->route == SPMM_ROUTE_AUTO || pl->route == SPMM_ROUTE_MFMA) to_mfma = true;
       else if (pl->route == SPMM_ROUTE_VALU) to_mfma = false;
-      else if (pl->route == SPMM_ROUTE_CLASS) to_mfma = cls != SPMM_LOW;
-      else to_mfma = !(cls == SPMM_LOW && low_to_csr);
+      else to_mfma = cls != SPMM_LOW && cls != 255;
       if (to_mfma) {
         mfma_panels.push_back((uint32_t)p);
         nbricks.push_back(pl->h_panel_ptr[p + 1] - pl->h_panel_ptr[p]);
