@@ -123,3 +123,26 @@ def test_noalloc_rejects_sizes_beyond_the_scratch(gpu):
     gpu.spmm_exec(plan, Bd, Cd)
     torch.cuda.synchronize()
     assert not bool(Cd.any())
+
+
+def test_noalloc_follows_the_plan_options(gpu):
+    """The opt-in modes (split-bf16 arithmetic, tile sharing for wide N, 32-row panels) go through
+    the same launcher, so the allocation-free entry point must give what spmm_exec gives."""
+    import torch
+    A = W.paired_panels(3000, cols_per_group=120, half_width=400, seed=73)
+    Bd = torch.from_numpy(W.dense_b(A.K, 256, 6)).cuda()
+    plan = _plan(gpu, A)
+    settings = [
+        ("bf16x3", lambda: gpu.spmm_plan_set_precision(plan, gpu.PRECISIONS["bf16x3"])),
+        ("fp32", lambda: gpu.spmm_plan_set_precision(plan, gpu.PRECISIONS["fp32"])),
+        ("tile sharing", lambda: gpu.spmm_plan_set_tile_sharing(plan, gpu.SHARE_WORKGROUP)),
+        ("32-row panels", lambda: gpu.spmm_plan_set_panel_height(plan, 32)),
+    ]
+    for name, apply in settings:
+        apply()
+        ref = gpu.spmm_exec(plan, Bd).clone()
+        out = torch.full_like(ref, float("nan"))
+        print(f"noalloc with {name}", flush=True)
+        assert _raw_noalloc(gpu, plan, Bd, out) == gpu.SPMM_OK, gpu.spmm_last_error()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), name
