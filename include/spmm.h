@@ -194,6 +194,8 @@ int spmm_plan_export(const spmm_plan_t *plan, uint32_t *panel_ptr /* host [P+1] 
  *                               the default, chosen by measurement on MI355X
  *   SPMM_SPLIT_EQ7_NEAREST (-1) parts_p = max(1, round-half-up(ratio_p)): the literal reading,
  *                               a panel is split from ratio 1.5
+ *   Under both Eq. 7 policies a part keeps at least 4 blocks (16 bricks): parts_p is capped
+ *   at blocks_p / 4, because splitting a smaller panel saves less than its merge costs.
  *   1                           never split
  *   parts > 1                   split every panel that has at least `parts` blocks into
  *                               `parts` (for tests of the merge path)

@@ -222,6 +222,8 @@ def test_auto_split_matches_oracle_partition(gpu, policy, M, N):
         got.setdefault(panel, []).append((int(b0), int(b1)))
     for p, want in zip(panels, parts):
         base = int(fmt["panel_ptr"][p])
+        # the library's own floor on top of Eq. 6-7: a part keeps at least 4 blocks (16 bricks)
+        want = min(want, max(1, -(-int(nb_p[p]) // 4) // 4))
         expect = [(base + lo, base + hi) for lo, hi in oracle.partition_ranges(int(nb_p[p]), want)]
         assert sorted(got[p]) == expect, p
     if M == 4000:
