@@ -36,8 +36,9 @@ enum spmm_status {
 enum spmm_route {
   SPMM_ROUTE_AUTO = 0,  /* the measured policy for MI355X: the MFMA brick kernel for every
                            panel (it loads each B row of a panel once, CSR loads it once per
-                           entry; on the fill x width map of config 5 the CSR kernel is
-                           nowhere ahead by more than a few percent)                         */
+                           entry; over the benchmark's sweep of brick fill 0.05..0.8 and
+                           N = 16..512 the CSR kernel is nowhere ahead by more than a few
+                           percent)                                                          */
   SPMM_ROUTE_MFMA = 1,  /* every panel through the MFMA brick kernel (an empty panel is a work
                            item without bricks that stores zeros)                            */
   SPMM_ROUTE_VALU = 2,  /* every panel through the vector-ALU CSR kernel                      */

@@ -218,9 +218,9 @@ int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
       const uint8_t cls = pl->h_panel_class[p];
       bool to_mfma;
       // AUTO is the measured policy for MI355X: the brick kernel loads each B row of a panel
-      // once where CSR loads it once per entry, and on the config-5 map (five fills x six
-      // widths) the CSR kernel is nowhere faster by more than a few percent (a tie at fill
-      // 0.05, N = 16), so every panel goes to the brick kernel.  SPMM_ROUTE_CLASS is the
+      // once where CSR loads it once per entry, and on the benchmark's sweep of brick fill
+      // (0.05..0.8) and width (16..512) the CSR kernel is nowhere faster by more than a few
+      // percent (a tie at fill 0.05, N = 16), so every panel goes to the brick kernel.  SPMM_ROUTE_CLASS is the
       // paper's per-class rule.
       // An empty panel (class 255) only needs its rows of C zeroed; either kernel does that, so
       // under CLASS it goes to the CSR kernel, whose launch the Low panels cause anyway.
@@ -251,7 +251,7 @@ int build_host_list(spmm_plan_t* pl, int64_t N, const HostList** out) {
         partition_counts(nm, nbricks.data(), nm * hl->info.n_tiles,
                          (int64_t)pl->num_cus * resident, pl->split, parts.data(), &waves);
         // A part keeps at least kMinBlocksPerPart blocks: splitting a panel of a few blocks saves
-        // less than the merge launch it causes (measured on config 5, fill 0.8: three panels of
+        // less than the merge launch it causes (measured on the 65,536-row sweep, fill 0.8: three panels of
         // about 20 bricks split in two, 24.8 us against 20.9 us unsplit).
         for (int64_t i = 0; i < nm; ++i) {
           const int64_t blocks = ceil_div(nbricks[i], kBrickK);
