@@ -338,19 +338,25 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
         for (int w = 0; w < V; ++w) st_b[s][qv * V + w] = tmp[w];
       }
     };
-    auto half = [&](float v, uint64_t mask, float4_t (&a_acc)[T], const float (&b)[T]) {
+    // the A operand of a brick: zero fill by its pattern, then the transposition
+    auto operand = [&](float v, uint64_t mask) {
       float in_bit_order;
       asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(in_bit_order) : "v"(v), "s"(mask));
-      const float a = __builtin_bit_cast(
+      return __builtin_bit_cast(
           float, __builtin_amdgcn_ds_bpermute(perm_transpose, __builtin_bit_cast(int, in_bit_order)));
+    };
+    auto multiply = [&](float a, float4_t (&a_acc)[T], const float (&b)[T]) {
 #pragma unroll
       for (int u = 0; u < T; ++u)
         a_acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[u], a_acc[u], 0, 0, 0);
     };
     auto compute = [&](int s) {   // the B operands of the stage serve both bricks
-      if (st_mt[s] != 0) half(st_at[s], st_mt[s], acc[0], st_b[s]);
-      if (st_mb[s] != 0) half(st_ab[s], st_mb[s], acc[1], st_b[s]);
+      if (st_mt[s] != 0) multiply(operand(st_at[s], st_mt[s]), acc[0], st_b[s]);
+      if (st_mb[s] != 0) multiply(operand(st_ab[s], st_mb[s]), acc[1], st_b[s]);
     };
+    // steady chunks: both operands of the next brick column are made one step early, under the
+    // current column's MFMAs (an empty half costs one wasted cross-lane move)
+    float at_ahead = 0.f, ab_ahead = 0.f;
 
     Chunk cur = load_meta(k_begin);
     uint32_t ro_cur = row_offset(load_col(k_begin));
@@ -369,7 +375,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
     auto step = [&](auto steady, int i, uint32_t g, const Chunk& m, uint32_t ro_this,
                     uint32_t col_following) {
       constexpr bool kSteady = decltype(steady)::value;
-      if (kSteady || (g >= (uint32_t)R && g - R < ncols)) compute(i % R);
+      if constexpr (kSteady) {
+        const int s = i % R, sn = (i + 1) % R;
+        const float at = at_ahead, ab = ab_ahead;
+        at_ahead = operand(st_at[sn], st_mt[sn]);
+        ab_ahead = operand(st_ab[sn], st_mb[sn]);
+        if (st_mt[s] != 0) multiply(at, acc[0], st_b[s]);
+        if (st_mb[s] != 0) multiply(ab, acc[1], st_b[s]);
+      } else {
+        if (g >= (uint32_t)R && g - R < ncols) compute(i % R);
+      }
       const uint32_t ro = ro_next;
       if (i + 1 < CH) {
         ro_next = __builtin_amdgcn_ds_bpermute(perm_base + 16u * (i + 1), ro_this);
@@ -393,6 +408,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void k_spmm_tm32(
     if (c + CH <= total) {
       chunk(std::false_type{});
       c += CH;
+    }
+    if (c + CH <= ncols) {   // c is a multiple of CH = R here, so stage 0 is next
+      at_ahead = operand(st_at[0], st_mt[0]);
+      ab_ahead = operand(st_ab[0], st_mb[0]);
     }
     for (; c + CH <= ncols; c += CH) chunk(std::true_type{});
     for (; c + CH <= total; c += CH) chunk(std::false_type{});
