@@ -103,7 +103,8 @@ int spmm_plan_update_values(spmm_plan_t *plan, const float *vals, void *stream);
  *       of A without entries become zero); must not overlap B
  *   stream  hipStream_t; the call only enqueues kernels and returns
  *
- * fp32 multiply, fp32 accumulate (no reduced-precision rounding of inputs).  The
+ * By default fp32 multiply and fp32 accumulate, no reduced-precision rounding of inputs
+ * (spmm_plan_set_precision offers split-bf16 arithmetic with its own stated bounds).  The
  * result is deterministic for a given plan, N and device.  The first call for a
  * new N builds and caches that N's work list (a host computation plus one small
  * upload, which synchronises the stream once); later calls allocate nothing.
